@@ -1,0 +1,67 @@
+"""Calibration of the synthetic workloads' static activation scales (test infrastructure).
+
+Runs the oracle's binary64 true-function encoder layer, without rounding any activation, over the
+seeded input of each named workload and records the largest magnitude of every activation that
+the int8 pipeline quantises (Section 3.2 step 1 of the paper: the input range of an operator is
+obtained by running the model).  scale = absmax / 127.  The softmax output P is the exception: it
+lies in [0, 1] whatever the input, so its scale is fixed at 1 / 127.
+
+Writes ``paper_2305_14405_amd/workload_scales.json``.  Calls nothing but the oracle and the input
+generator.  Usage: python -m oracle.make_scales [workload ...]
+"""
+from __future__ import annotations
+
+import json
+import os
+import sys
+import time
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+from oracle import oracle as O  # noqa: E402
+from paper_2305_14405_amd import workloads as W  # noqa: E402
+
+_FUNC = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
+# batch used for calibration: activations are i.i.d. over sequences, a few are enough
+CALIB_BATCH = {"bert_base_s512": 2, "bert_large_s512": 1}
+DEFAULT = ("tiny", "ragged", "bert_base_layer", "bert_base_s512", "bert_large_s512")
+
+
+def oracle_tables(cfg):
+    return {n: O.build_table(_FUNC[f], lo, hi, nseg)
+            for n, (f, lo, hi, nseg) in W.table_ranges(cfg).items()}
+
+
+def calibrate(name: str, seed: int = 0) -> dict:
+    cfg = W.config(name)
+    t = W.layer_tensors(cfg, seed)
+    if name in CALIB_BATCH:
+        nb = CALIB_BATCH[name]
+        t["x"] = t["x"][: nb * cfg["S"]].copy()
+        t["B"] = nb
+    p = W.with_scales(t, W.unit_scales())
+    _, obs = O.encoder_layer_exact(p, oracle_tables(cfg), t["x"], quantise=False)
+    scales = {n: obs[n] / 127.0 for n in W.ACT_NAMES}
+    scales["p"] = 1.0 / 127.0
+    scales["observed"] = obs
+    return scales
+
+
+def main(argv):
+    names = argv or DEFAULT
+    table = {}
+    if os.path.exists(W.SCALES_JSON):
+        with open(W.SCALES_JSON) as f:
+            table = json.load(f)
+    for name in names:
+        t0 = time.time()
+        table[f"{name}/seed0"] = calibrate(name, 0)
+        print(f"{name}: {time.time() - t0:.1f} s", {k: round(v, 5) for k, v in
+                                                    table[f'{name}/seed0'].items()
+                                                    if k != "observed"}, flush=True)
+    with open(W.SCALES_JSON, "w") as f:
+        json.dump(table, f, indent=1, sort_keys=True)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:])

@@ -1,0 +1,198 @@
+"""Seeded synthetic workloads: the only module shared by the GPU library's harness and the CPU
+oracle's tests.  It generates INPUTS (int8 tensors, fp32 vectors, scale numbers, table ranges); it
+holds none of the method's arithmetic (no GEMM, no PWL evaluation, no reductions).
+
+The tensors stand in for the workloads the paper evaluates (BERT / RoBERTa encoders on GLUE):
+random-initialised weights and random inputs with the shapes of those models.  Recipe:
+
+* one ``numpy`` PCG64 stream per (workload, seed), drawn in the fixed order
+  x, Wqkv, bqkv, Wo, bo, gamma1, beta1, W1, b1, W2, b2, gamma2, beta2;
+* weights ~ N(0, 0.02^2), input x ~ N(0, 1), biases and beta ~ N(0, 0.02^2),
+  gamma ~ 1 + N(0, 0.02^2)  (non-trivial so that every epilogue term is exercised);
+* int8 tensors are per-tensor symmetric: scale = absmax / 127, code = clip(rint(v / scale));
+* activation scales are static.  They come from ``workload_scales.json`` (written once by the
+  calibration script that sits with the CPU oracle: one run of the true-function network over the
+  same seeded input, scale = observed absmax / 127; this is step 1 of the paper's Section 3.2,
+  "obtain the input range by running the model", applied to scales as well as to table ranges).
+"""
+from __future__ import annotations
+
+import json
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+SCALES_JSON = os.path.join(_HERE, "workload_scales.json")
+
+# name -> dims, segment count, PWL ranges (function name, lo, hi)
+CONFIGS = {
+    # BASELINE config 0: the small case the oracle finishes in well under a second
+    "tiny": dict(B=1, S=64, H=128, heads=2, F=512, nseg=64),
+    # BASELINE config 1: the configuration the headline metric is quoted on
+    "bert_base_layer": dict(B=32, S=128, H=768, heads=12, F=3072, nseg=128),
+    # one layer of BASELINE config 2 (12-layer BERT-base, batch 16, sequence 512)
+    "bert_base_s512": dict(B=16, S=512, H=768, heads=12, F=3072, nseg=128),
+    # one layer of BASELINE config 4 (24-layer BERT-large, batch 32, sequence 512)
+    "bert_large_s512": dict(B=32, S=512, H=1024, heads=16, F=4096, nseg=64),
+    # ragged shapes that fit no tile exactly (parity tests only)
+    "ragged": dict(B=3, S=40, H=96, heads=3, F=200, nseg=37),
+}
+
+ACT_NAMES = ("q", "k", "v", "p", "ctx", "ln1", "ffn1", "out")
+
+LAYER_FLOATS = ("alpha_qkv", "inv_s_q", "inv_s_k", "inv_s_v", "alpha_scores", "inv_s_p",
+                "alpha_ctx", "inv_s_ctx", "alpha_o", "resid1_scale", "inv_s_ln1", "alpha_1",
+                "inv_s_ffn1", "alpha_2", "resid2_scale", "inv_s_out")
+
+
+def config(name: str) -> dict:
+    return dict(CONFIGS[name])
+
+
+def table_ranges(cfg: dict) -> dict:
+    """PWL ranges of BASELINE's configs: GELU on [-8, 8], exp on [-16, 0], reciprocal on
+    [1, max(64, S)] (a softmax denominator lies in [1, S]), rsqrt on [1e-3, 64]."""
+    n = int(cfg["nseg"])
+    return {
+        "gelu": ("gelu", -8.0, 8.0, n),
+        "exp": ("exp", -16.0, 0.0, n),
+        "recip": ("recip", 1.0, float(max(64, cfg["S"])), n),
+        "rsqrt": ("rsqrt", 1e-3, 64.0, n),
+    }
+
+
+def quantize_sym(v: np.ndarray):
+    """Per-tensor symmetric int8 code of a synthetic tensor: (codes, scale)."""
+    amax = float(np.max(np.abs(v)))
+    scale = amax / 127.0 if amax > 0 else 1.0
+    q = np.clip(np.rint(v.astype(np.float64) / scale), -127, 127).astype(np.int8)
+    return q, scale
+
+
+def layer_tensors(cfg: dict, seed: int = 0) -> dict:
+    """All tensors of one encoder layer and its input, quantised, plus their scales."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    B, S, H, F = cfg["B"], cfg["S"], cfg["H"], cfg["F"]
+    M = B * S
+
+    def normal(shape, std, mean=0.0):
+        return (mean + std * g.standard_normal(shape, dtype=np.float32)).astype(np.float32)
+
+    t = dict(B=B, S=S, H=H, heads=cfg["heads"], F=F)
+    x = normal((M, H), 1.0)
+    t["x"], t["s_x"] = quantize_sym(x)
+    t["Wqkv"], t["s_wqkv"] = quantize_sym(normal((3 * H, H), 0.02))
+    t["bqkv"] = normal((3 * H,), 0.02)
+    t["Wo"], t["s_wo"] = quantize_sym(normal((H, H), 0.02))
+    t["bo"] = normal((H,), 0.02)
+    t["gamma1"] = normal((H,), 0.02, 1.0)
+    t["beta1"] = normal((H,), 0.02)
+    t["W1"], t["s_w1"] = quantize_sym(normal((F, H), 0.02))
+    t["b1"] = normal((F,), 0.02)
+    t["W2"], t["s_w2"] = quantize_sym(normal((H, F), 0.02))
+    t["b2"] = normal((H,), 0.02)
+    t["gamma2"] = normal((H,), 0.02, 1.0)
+    t["beta2"] = normal((H,), 0.02)
+    t["eps1"] = 1e-5
+    t["eps2"] = 1e-5
+    return t
+
+
+def with_scales(t: dict, act: dict) -> dict:
+    """Add the fp32 multipliers both implementations receive, formed in binary64 from the tensor
+    scales and rounded once to fp32.  ``act`` maps q,k,v,p,ctx,ln1,ffn1,out -> scale."""
+    p = dict(t)
+    d = t["H"] // t["heads"]
+    f32 = lambda v: float(np.float32(v))  # noqa: E731
+    p["alpha_qkv"] = f32(t["s_x"] * t["s_wqkv"])
+    p["inv_s_q"] = f32(1.0 / act["q"])
+    p["inv_s_k"] = f32(1.0 / act["k"])
+    p["inv_s_v"] = f32(1.0 / act["v"])
+    p["alpha_scores"] = f32(act["q"] * act["k"] / np.sqrt(float(d)))
+    p["inv_s_p"] = f32(1.0 / act["p"])
+    p["alpha_ctx"] = f32(act["p"] * act["v"])
+    p["inv_s_ctx"] = f32(1.0 / act["ctx"])
+    p["alpha_o"] = f32(act["ctx"] * t["s_wo"])
+    p["resid1_scale"] = f32(t["s_x"])
+    p["inv_s_ln1"] = f32(1.0 / act["ln1"])
+    p["alpha_1"] = f32(act["ln1"] * t["s_w1"])
+    p["inv_s_ffn1"] = f32(1.0 / act["ffn1"])
+    p["alpha_2"] = f32(act["ffn1"] * t["s_w2"])
+    p["resid2_scale"] = f32(act["ln1"])
+    p["inv_s_out"] = f32(1.0 / act["out"])
+    p["act_scales"] = dict(act)
+    return p
+
+
+def unit_scales() -> dict:
+    return {n: 1.0 for n in ACT_NAMES}
+
+
+def stored_scales(name: str, seed: int = 0) -> dict:
+    """Calibrated activation scales of a named workload, from the stored calibration file."""
+    with open(SCALES_JSON) as f:
+        table = json.load(f)
+    key = f"{name}/seed{seed}"
+    if key not in table:
+        raise KeyError(f"no stored activation scales for {key}; run oracle/make_scales.py")
+    return {n: float(table[key][n]) for n in ACT_NAMES}
+
+
+def layer_params(name: str, seed: int = 0) -> dict:
+    """Tensors + calibrated multipliers of a named workload."""
+    return with_scales(layer_tensors(config(name), seed), stored_scales(name, seed))
+
+
+# ---------------------------------------------------------------------------------------------
+# Inputs for the single-kernel tests and for the stress distribution (values that sweep the whole
+# table range, fall outside it, sit on break points, constant rows).
+# ---------------------------------------------------------------------------------------------
+
+def gemm_inputs(M: int, N: int, K: int, seed: int = 0, full_range: bool = True) -> dict:
+    g = np.random.Generator(np.random.PCG64(seed))
+    lim = 127 if full_range else 20
+    return dict(
+        A=g.integers(-lim, lim + 1, size=(M, K), dtype=np.int8),
+        W=g.integers(-lim, lim + 1, size=(N, K), dtype=np.int8),
+        bias=(0.5 * g.standard_normal(N)).astype(np.float32),
+        resid=g.integers(-127, 128, size=(M, N), dtype=np.int8),
+        alpha_vec=np.exp(0.25 * g.standard_normal(N)).astype(np.float32),
+        out_inv_scale_vec=np.exp(0.25 * g.standard_normal(N)).astype(np.float32),
+    )
+
+
+def score_rows(rows: int, cols: int, seed: int = 0, spread: float = 4000.0) -> np.ndarray:
+    """int32 attention-score-like rows; a few rows are constant, a few have outliers far below
+    the exp table's range."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    a = np.rint(spread * g.standard_normal((rows, cols))).astype(np.int32)
+    if rows >= 4:
+        a[1, :] = 1234
+        a[2, :: max(1, cols // 7)] -= 10_000_000
+        a[3, 0] += 5_000_000
+    return a
+
+
+def float_rows(rows: int, cols: int, seed: int = 0, std: float = 1.5) -> np.ndarray:
+    """fp32 LayerNorm-input-like rows; includes a constant row, a tiny-variance row and a
+    large-variance row."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    a = (std * g.standard_normal((rows, cols))).astype(np.float32)
+    if rows >= 4:
+        a[1, :] = 0.75
+        a[2, :] = 3.0 + 1e-3 * a[2, :]
+        a[3, :] *= 9.0
+    return a
+
+
+def sweep_values(lo: float, hi: float, n: int, seed: int = 0) -> np.ndarray:
+    """fp32 values that cover [lo - 10%, hi + 10%] densely, plus the exact break points of an
+    n-independent dyadic grid and a few specials (0, -0, huge)."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    span = hi - lo
+    v = g.uniform(lo - 0.1 * span, hi + 0.1 * span, size=n).astype(np.float32)
+    grid = np.linspace(lo, hi, 257, dtype=np.float64).astype(np.float32)
+    specials = np.array([0.0, -0.0, lo, hi, 1e30, -1e30, np.nextafter(np.float32(hi), np.float32(0))],
+                        dtype=np.float32)
+    return np.concatenate([v, grid, specials]).astype(np.float32)
