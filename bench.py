@@ -1,0 +1,186 @@
+"""Benchmark of the PWL int8 encoder layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_base_layer]
+
+A step is one pass of the whole hot path (nm_encoder_layer: QKV GEMM, scores, softmax-PWL, context,
+output projection, LayerNorm-PWL, FFN1 + GELU-PWL, FFN2, LayerNorm-PWL) over one batch of seeded
+synthetic input that already sits in HBM.  Prints ONE JSON line: sequences/s, per-kernel roofline
+figures measured live with HIP events on the launch stream, and the CPU oracle timed on the host
+cores over the same workload (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, published: 5.0 POP/s
+PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published: 8 TB/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="bert_base_layer")
+    ap.add_argument("--kernel-reps", type=int, default=50)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2305_14405_amd import binding as nm
+    from paper_2305_14405_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = W.config(args.workload)
+    p = W.layer_params(args.workload, 0)
+    B, S, H, nh, F = (cfg[k] for k in ("B", "S", "H", "heads", "F"))
+    M, d = B * S, cfg["H"] // cfg["heads"]
+    order = ("gelu", "exp", "recip", "rsqrt")
+    specs = [W.table_ranges(cfg)[n] for n in order]
+    tables = nm.nm_build_tables(specs)          # the library's own table builder
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)  # noqa: E731
+    devw = {n: t(p[n]) for n in nm.LAYER_PTRS}
+    desc = nm.make_layer_desc(p, devw, tables)
+    ws = torch.empty(nm.nm_encoder_layer_workspace(desc), dtype=torch.uint8, device=dev)
+    x = t(p["x"])
+    yq = torch.empty((M, H), dtype=torch.int8, device=dev)
+    taps = dict(qkv=torch.empty((M, 3 * H), dtype=torch.int8, device=dev),
+                scores=torch.empty((B, nh, S, S), dtype=torch.int32, device=dev),
+                p=torch.empty((B, nh, S, S), dtype=torch.int8, device=dev),
+                ctx=torch.empty((M, H), dtype=torch.int8, device=dev),
+                attn=torch.empty((M, H), dtype=torch.float32, device=dev),
+                ln1=torch.empty((M, H), dtype=torch.int8, device=dev),
+                ffn1=torch.empty((M, F), dtype=torch.int8, device=dev),
+                ffn2=torch.empty((M, H), dtype=torch.float32, device=dev))
+
+    def step():
+        nm.nm_encoder_layer(desc, x, yq, None, ws, taps=taps)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    seq_per_s = B / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations, HIP events on the launch stream (torch's current stream) ------
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps  # ms
+
+    osv = t(np.concatenate([np.full(H, p["inv_s_q"]), np.full(H, p["inv_s_k"]),
+                            np.full(H, p["inv_s_v"])]).astype(np.float32))
+    stages = [
+        ("qkv_gemm", "mfma", 2.0 * M * 3 * H * H,
+         lambda: nm.nm_gemm_pwl(x, devw["Wqkv"], bias=devw["bqkv"], alpha=p["alpha_qkv"],
+                                out_inv_scale_vec=osv, out_q=taps["qkv"])),
+        ("attn_scores", "hbm", float(M * 2 * H + B * nh * S * S * 4),
+         lambda: nm.nm_attn_scores(taps["qkv"], B, S, H, nh, taps["scores"])),
+        ("softmax_pwl", "hbm", float(B * nh * S * S * 5),
+         lambda: nm.nm_softmax_pwl(taps["scores"].view(-1, S), p["alpha_scores"], tables, 1, 2,
+                                   p["inv_s_p"], out_q=taps["p"].view(-1, S))),
+        ("attn_context", "hbm", float(B * nh * S * S + M * H + M * H),
+         lambda: nm.nm_attn_context(taps["p"], taps["qkv"], B, S, H, nh, p["alpha_ctx"],
+                                    p["inv_s_ctx"], taps["ctx"])),
+        ("out_proj_gemm", "mfma", 2.0 * M * H * H,
+         lambda: nm.nm_gemm_pwl(taps["ctx"], devw["Wo"], bias=devw["bo"], alpha=p["alpha_o"],
+                                resid=x, resid_scale=p["resid1_scale"], out_f32=taps["attn"])),
+        ("layernorm_pwl", "hbm", float(M * H * 5),
+         lambda: nm.nm_layernorm_pwl(taps["attn"], devw["gamma1"], devw["beta1"], p["eps1"], tables,
+                                     3, p["inv_s_ln1"], out_q=taps["ln1"])),
+        ("ffn1_gelu_gemm", "mfma", 2.0 * M * F * H,
+         lambda: nm.nm_gemm_pwl(taps["ln1"], devw["W1"], bias=devw["b1"], alpha=p["alpha_1"],
+                                tables=tables, table_idx=0, out_inv_scale=p["inv_s_ffn1"],
+                                out_q=taps["ffn1"])),
+        ("ffn2_gemm", "mfma", 2.0 * M * H * F,
+         lambda: nm.nm_gemm_pwl(taps["ffn1"], devw["W2"], bias=devw["b2"], alpha=p["alpha_2"],
+                                resid=taps["ln1"], resid_scale=p["resid2_scale"],
+                                out_f32=taps["ffn2"])),
+    ]
+    kernels = []
+    for name, bound, work, fn in stages:
+        ms = timed(fn, args.kernel_reps)
+        if bound == "mfma":
+            ach, peak, unit = work / (ms * 1e-3) / 1e12, PEAK_INT8_TOPS, "TFLOP/s"
+        else:
+            ach, peak, unit = work / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        kernels.append(dict(kernel=name, bound=bound, ms=round(ms, 5), achieved=round(ach, 2),
+                            peak=peak, unit=unit, frac=round(ach / peak, 4)))
+    dom = max(kernels, key=lambda k: k["ms"])
+    roofline = dict(bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"], unit=dom["unit"],
+                    frac=dom["frac"], traffic=None, kernel=dom["kernel"],
+                    note="int8 MFMA rate in TOP/s (2 ops per multiply-accumulate)")
+    gemm_ops = sum(2.0 * M * n * k for n, k in ((3 * H, H), (H, H), (F, H), (H, F)))
+    gemm_ms = sum(k["ms"] for k in kernels if k["bound"] == "mfma")
+    row_bytes = float(B * nh * S * S * 5 + 2 * M * H * 5)
+    row_ms = sum(k["ms"] for k in kernels if k["kernel"] in ("softmax_pwl", "layernorm_pwl")) + \
+        next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl")
+    summary = dict(int8_mfma_util_pct=round(100 * gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
+                   nonlinear_hbm_gbs=round(row_bytes / (row_ms * 1e-3) / 1e9, 1),
+                   sum_kernel_ms=round(sum(k["ms"] for k in kernels) +
+                                       next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl"), 4))
+
+    # ---- CPU oracle on the host cores: the same workload, bounded sample ----------------------
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        oid = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
+        ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3]) for n, s in zip(order, specs)}
+        n_layers, c0 = 0, time.perf_counter()
+        while True:
+            want = O.encoder_layer(p, ot, p["x"], want_taps=False)
+            n_layers += 1
+            if time.perf_counter() - c0 > 10.0 or n_layers >= 8:
+                break
+        cpu_s = (time.perf_counter() - c0) / n_layers
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu_baseline = dict(value=round(B / cpu_s, 3), unit="sequences/s", cores=cores, kind="oracle",
+                            sample=f"{n_layers} full {args.workload} layer(s), B={B} sequences each, "
+                                   f"{cpu_s:.2f} s per layer")
+        # the library built its own tables: compare with the oracle's layer (1 LSB allowance)
+        step()
+        torch.cuda.synchronize()
+        diff = np.abs(yq.cpu().numpy().astype(int) - want["y_q"].astype(int))
+        parity = dict(int8_max_abs_diff=int(diff.max()), int8_mismatch_frac=float((diff > 0).mean()),
+                      note="library-built tables vs oracle-built tables (may differ in the last bit)")
+
+    out = dict(metric="PWL encoder-layer sequences/s + int8 MFMA util % + nonlinear-kernel HBM GB/s",
+               value=round(seq_per_s, 1), unit="sequences/s", n_gpus=1, steps=args.steps,
+               warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True,
+               scaling="weak", vs_baseline=None, dtype="int8 (int32 accumulate, fp32 epilogue)",
+               data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
+                                             nseg=cfg["nseg"], layers=1),
+               roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, summary=summary,
+               parity=parity)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,305 @@
+"""Thin ctypes binding of the C ABI in ``include/nm.h``: argument marshalling only.
+
+Functions carry the names of the C entry points.  Tensors are ``torch`` device tensors (PyTorch is
+used for device memory and streams only); every step of the computation runs in the HIP library.
+There is no fallback: if ``libnm_hip.so`` is missing the import of the library fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libnm_hip.so")
+
+NM_OK = 0
+NM_ERR_INVALID_ARG, NM_ERR_UNSUPPORTED, NM_ERR_ALLOC, NM_ERR_HIP, NM_ERR_WORKSPACE = -1, -2, -3, -4, -5
+FUNC = {"gelu": 0, "exp": 1, "recip": 2, "rsqrt": 3, "relu": 4, "sqrt": 5, "identity": 6}
+NM_TABLE_CLAMP_INPUT, NM_TABLE_BIAS_CORRECT, NM_TABLE_MERGE = 1, 2, 4
+NM_DT_I32, NM_DT_F32 = 0, 1
+
+# every symbol include/nm.h declares
+EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_tables",
+           "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_destroy",
+           "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_pwl_apply", "nm_attn_scores",
+           "nm_attn_context", "nm_encoder_layer_workspace", "nm_encoder_layer")
+
+
+class NmError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"nm status {status}: {message}")
+        self.status = status
+
+
+class TableDesc(C.Structure):
+    _fields_ = [("func", C.c_int32), ("lo", C.c_float), ("hi", C.c_float), ("nseg", C.c_int32),
+                ("flags", C.c_int32), ("e_th", C.c_float), ("dk_th", C.c_float)]
+
+
+class GemmDesc(C.Structure):
+    _fields_ = [("M", C.c_int32), ("N", C.c_int32), ("K", C.c_int32), ("A", C.c_void_p),
+                ("W", C.c_void_p), ("bias", C.c_void_p), ("alpha_vec", C.c_void_p),
+                ("alpha", C.c_float), ("resid", C.c_void_p), ("resid_scale", C.c_float),
+                ("tables", C.c_void_p), ("table_idx", C.c_int32), ("out_inv_scale", C.c_float),
+                ("out_inv_scale_vec", C.c_void_p), ("out_q", C.c_void_p), ("out_f32", C.c_void_p),
+                ("out_acc", C.c_void_p), ("dbg_seg", C.c_void_p)]
+
+
+LAYER_FLOATS = ("alpha_qkv", "inv_s_q", "inv_s_k", "inv_s_v", "alpha_scores", "inv_s_p",
+                "alpha_ctx", "inv_s_ctx", "alpha_o", "resid1_scale", "inv_s_ln1", "alpha_1",
+                "inv_s_ffn1", "alpha_2", "resid2_scale", "inv_s_out")
+LAYER_PTRS = ("Wqkv", "bqkv", "Wo", "bo", "W1", "b1", "W2", "b2", "gamma1", "beta1", "gamma2",
+              "beta2")
+TAP_NAMES = ("qkv", "scores", "p", "ctx", "attn", "ln1", "ffn1", "ffn2")
+
+
+class LayerDesc(C.Structure):
+    _fields_ = ([(n, C.c_int32) for n in ("B", "S", "H", "heads", "F")] +
+                [(n, C.c_void_p) for n in LAYER_PTRS] +
+                [("eps1", C.c_float), ("eps2", C.c_float)] +
+                [(n, C.c_float) for n in LAYER_FLOATS] +
+                [("tables", C.c_void_p)] +
+                [(n, C.c_int32) for n in ("gelu_idx", "exp_idx", "recip_idx", "rsqrt_idx")])
+
+
+class LayerTaps(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in TAP_NAMES]
+
+
+_lib = None
+
+
+def load(preload_torch: bool = True) -> C.CDLL:
+    """Load libnm_hip.so.  torch is imported first so that the process uses one HIP runtime."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with "
+                          "`python -m paper_2305_14405_amd.build` (there is no CPU fallback)")
+    if preload_torch:
+        import torch  # noqa: F401
+    L = C.CDLL(LIB_PATH)
+    L.nm_last_error.restype = C.c_char_p
+    L.nm_table_build_host.argtypes = [C.POINTER(TableDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p]
+    L.nm_build_tables.argtypes = [C.POINTER(TableDesc), C.c_int32, C.c_void_p,
+                                  C.POINTER(C.c_void_p)]
+    L.nm_tables_from_arrays.argtypes = [C.POINTER(TableDesc), C.c_int32, C.POINTER(C.c_void_p),
+                                        C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_void_p)]
+    L.nm_tables_count.argtypes = [C.c_void_p]
+    L.nm_tables_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(TableDesc), C.c_void_p,
+                                C.c_void_p, C.c_void_p]
+    L.nm_tables_destroy.argtypes = [C.c_void_p]
+    L.nm_tables_destroy.restype = None
+    L.nm_gemm_pwl.argtypes = [C.POINTER(GemmDesc), C.c_void_p]
+    L.nm_softmax_pwl.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int64, C.c_int32,
+                                 C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.nm_layernorm_pwl.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int64,
+                                   C.c_int32, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.c_void_p]
+    L.nm_pwl_apply.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int64, C.c_void_p, C.c_int32,
+                               C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.nm_attn_scores.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                 C.c_void_p, C.c_void_p]
+    L.nm_attn_context.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
+    L.nm_encoder_layer_workspace.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_size_t)]
+    L.nm_encoder_layer.argtypes = [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_size_t, C.POINTER(LayerTaps), C.c_void_p]
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != NM_OK:
+        raise NmError(rc, load().nm_last_error().decode())
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / None."""
+    if t is None:
+        return None
+    if hasattr(t, "data_ptr"):
+        assert t.is_contiguous(), "tensors passed to the C ABI must be contiguous"
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def nm_last_error() -> str:
+    return load().nm_last_error().decode()
+
+
+def nm_version() -> int:
+    return load().nm_version()
+
+
+def _desc(spec) -> TableDesc:
+    """spec: (func name or id, lo, hi, nseg[, flags[, e_th[, dk_th]]])."""
+    func, lo, hi, nseg, *rest = spec
+    flags = rest[0] if len(rest) > 0 else 0
+    e_th = rest[1] if len(rest) > 1 else 0.0
+    dk_th = rest[2] if len(rest) > 2 else 0.0
+    fid = FUNC[func] if isinstance(func, str) else int(func)
+    return TableDesc(fid, lo, hi, nseg, flags, e_th, dk_th)
+
+
+def nm_table_build_host(spec):
+    """Host-only table construction.  Returns (k, b, inv_w, n_distinct) as numpy values."""
+    import numpy as np
+    d = _desc(spec)
+    n = max(int(d.nseg), 1)
+    k = np.zeros(n, np.float32)
+    b = np.zeros(n, np.float32)
+    inv_w = np.zeros(1, np.float32)
+    nd = np.zeros(1, np.int32)
+    _check(load(preload_torch=False).nm_table_build_host(C.byref(d), k.ctypes.data, b.ctypes.data,
+                                                         inv_w.ctypes.data, nd.ctypes.data))
+    return k, b, inv_w[0], int(nd[0])
+
+
+class Tables:
+    """Owner of an nm_tables object."""
+
+    def __init__(self, handle, n):
+        self.handle = handle
+        self.n = n
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.nm_tables_destroy(self.handle)
+            self.handle = None
+
+
+def nm_build_tables(specs, stream=None) -> Tables:
+    arr = (TableDesc * len(specs))(*[_desc(s) for s in specs])
+    out = C.c_void_p()
+    _check(load().nm_build_tables(arr, len(specs), _stream(stream), C.byref(out)))
+    return Tables(out.value, len(specs))
+
+
+def nm_tables_from_arrays(specs, ks, bs, stream=None) -> Tables:
+    import numpy as np
+    arr = (TableDesc * len(specs))(*[_desc(s) for s in specs])
+    ks = [np.ascontiguousarray(k, np.float32) for k in ks]
+    bs = [np.ascontiguousarray(b, np.float32) for b in bs]
+    kp = (C.c_void_p * len(specs))(*[k.ctypes.data for k in ks])
+    bp = (C.c_void_p * len(specs))(*[b.ctypes.data for b in bs])
+    out = C.c_void_p()
+    _check(load().nm_tables_from_arrays(arr, len(specs), kp, bp, _stream(stream), C.byref(out)))
+    return Tables(out.value, len(specs))
+
+
+def nm_tables_count(t: Tables) -> int:
+    return load().nm_tables_count(t.handle if t else None)
+
+
+def nm_tables_get(t: Tables, idx: int):
+    import numpy as np
+    d = TableDesc()
+    _check(load().nm_tables_get(t.handle, idx, C.byref(d), None, None, None))
+    k = np.zeros(d.nseg, np.float32)
+    b = np.zeros(d.nseg, np.float32)
+    inv_w = np.zeros(1, np.float32)
+    _check(load().nm_tables_get(t.handle, idx, None, k.ctypes.data, b.ctypes.data,
+                                inv_w.ctypes.data))
+    return d, k, b, inv_w[0]
+
+
+def nm_gemm_pwl(A, W, *, bias=None, alpha=1.0, alpha_vec=None, resid=None, resid_scale=0.0,
+                tables: Tables | None = None, table_idx=-1, out_inv_scale=1.0,
+                out_inv_scale_vec=None, out_q=None, out_f32=None, out_acc=None, dbg_seg=None,
+                stream=None, M=None, N=None, K=None):
+    d = GemmDesc()
+    d.M = A.shape[0] if M is None else M
+    d.K = A.shape[1] if K is None else K
+    d.N = W.shape[0] if N is None else N
+    d.A, d.W, d.bias, d.alpha_vec = _ptr(A), _ptr(W), _ptr(bias), _ptr(alpha_vec)
+    d.alpha = alpha
+    d.resid, d.resid_scale = _ptr(resid), resid_scale
+    d.tables = tables.handle if tables is not None else None
+    d.table_idx = table_idx
+    d.out_inv_scale = out_inv_scale
+    d.out_inv_scale_vec = _ptr(out_inv_scale_vec)
+    d.out_q, d.out_f32, d.out_acc, d.dbg_seg = _ptr(out_q), _ptr(out_f32), _ptr(out_acc), _ptr(dbg_seg)
+    _check(load().nm_gemm_pwl(C.byref(d), _stream(stream)))
+
+
+def nm_softmax_pwl(x, alpha, tables: Tables, exp_idx, recip_idx, out_inv_scale, *, out_q=None,
+                   out_f32=None, dbg_seg_exp=None, dbg_seg_recip=None, stream=None, rows=None,
+                   cols=None):
+    import torch
+    dt = NM_DT_I32 if x.dtype == torch.int32 else NM_DT_F32
+    rows = x.shape[0] if rows is None else rows
+    cols = x.shape[1] if cols is None else cols
+    _check(load().nm_softmax_pwl(_ptr(x), dt, alpha, rows, cols, tables.handle, exp_idx, recip_idx,
+                                 out_inv_scale, _ptr(out_q), _ptr(out_f32), _ptr(dbg_seg_exp),
+                                 _ptr(dbg_seg_recip), _stream(stream)))
+
+
+def nm_layernorm_pwl(x, gamma, beta, eps, tables: Tables, rsqrt_idx, out_inv_scale, *, out_q=None,
+                     out_f32=None, dbg_seg=None, stream=None, rows=None, cols=None):
+    rows = x.shape[0] if rows is None else rows
+    cols = x.shape[1] if cols is None else cols
+    _check(load().nm_layernorm_pwl(_ptr(x), _ptr(gamma), _ptr(beta), eps, rows, cols,
+                                   tables.handle, rsqrt_idx, out_inv_scale, _ptr(out_q),
+                                   _ptr(out_f32), _ptr(dbg_seg), _stream(stream)))
+
+
+def nm_pwl_apply(x, alpha, tables: Tables, idx, out_inv_scale, *, out_q=None, out_f32=None,
+                 dbg_seg=None, stream=None, n=None):
+    import torch
+    dt = NM_DT_I32 if x.dtype == torch.int32 else NM_DT_F32
+    n = x.numel() if n is None else n
+    _check(load().nm_pwl_apply(_ptr(x), dt, alpha, n, tables.handle, idx, out_inv_scale,
+                               _ptr(out_q), _ptr(out_f32), _ptr(dbg_seg), _stream(stream)))
+
+
+def nm_attn_scores(qkv, B, S, H, heads, scores, stream=None):
+    _check(load().nm_attn_scores(_ptr(qkv), B, S, H, heads, _ptr(scores), _stream(stream)))
+
+
+def nm_attn_context(p, qkv, B, S, H, heads, alpha, out_inv_scale, ctx, stream=None):
+    _check(load().nm_attn_context(_ptr(p), _ptr(qkv), B, S, H, heads, alpha, out_inv_scale,
+                                  _ptr(ctx), _stream(stream)))
+
+
+def make_layer_desc(params: dict, dev: dict, tables: Tables, idx=(0, 1, 2, 3)) -> LayerDesc:
+    """params: numbers (dims, eps, fp32 multipliers); dev: device tensors of the weights."""
+    d = LayerDesc()
+    for n in ("B", "S", "H", "heads", "F"):
+        setattr(d, n, int(params[n]))
+    for n in LAYER_PTRS:
+        setattr(d, n, _ptr(dev[n]))
+    d.eps1, d.eps2 = float(params["eps1"]), float(params["eps2"])
+    for n in LAYER_FLOATS:
+        setattr(d, n, float(params[n]))
+    d.tables = tables.handle
+    d.gelu_idx, d.exp_idx, d.recip_idx, d.rsqrt_idx = idx
+    return d
+
+
+def nm_encoder_layer_workspace(desc: LayerDesc) -> int:
+    n = C.c_size_t()
+    _check(load().nm_encoder_layer_workspace(C.byref(desc), C.byref(n)))
+    return n.value
+
+
+def nm_encoder_layer(desc: LayerDesc, x, y_q, y_f32, ws, taps: dict | None = None, stream=None,
+                     ws_bytes=None):
+    ct = None
+    if taps:
+        ct = LayerTaps()
+        for n in TAP_NAMES:
+            setattr(ct, n, _ptr(taps.get(n)))
+    nbytes = ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes
+    _check(load().nm_encoder_layer(C.byref(desc), _ptr(x), _ptr(y_q), _ptr(y_f32), _ptr(ws), nbytes,
+                                   C.byref(ct) if ct is not None else None, _stream(stream)))

@@ -1,0 +1,382 @@
+// int8 x int8 -> int32 GEMM on the gfx950 matrix cores with the fused epilogue
+// (dequantise, bias, residual, PWL table lookup from LDS, requantise), plus the two attention
+// products, which are the same kernel launched over (batch, head) with strided operands.
+//
+// Paper basis: Section 3.1 (fully connected layers, attention and residual additions are matrix
+// multiplications / additions) and Section 3.2 (the nonlinearity after a linear operator is the
+// element-wise PWL calculation y = k[s]*x + b[s]).  The paper blocks its matrices for a systolic
+// array with a three-level buffer hierarchy; here the blocking is for CDNA4: a workgroup of four
+// wavefronts owns a BM x BN tile of the output, the k-loop streams 64-byte slices of both operands
+// through double-buffered LDS, and each wavefront issues 32x32x32 int8 MFMAs on its WM x WN
+// sub-tile with int32 accumulators that never leave registers until the epilogue.
+//
+// Operand roles: the MFMA's first operand supplies the rows of its 32x32 result and the second
+// the columns.  W rows (output columns n) go first and A rows (output rows m) second, so a lane
+// ends up with one output row m and, per group of four accumulator registers, four consecutive
+// output columns n: four int8 results pack into one 32-bit store and bias / per-column scales
+// are read as four consecutive floats.
+//
+// Both operands are K-contiguous, which is what the int8 MFMA wants: a lane feeds 16 consecutive
+// k of one row.  The same k of A and W always meet in the same (lane group, byte) slot, and int32
+// addition is exact, so results do not depend on tiling, on the k order or on any split of K.
+#include "nm_device.h"
+
+namespace nm {
+
+constexpr int kGemmThreads = 256;
+constexpr int kBK = 64;  // bytes of k per pipeline stage
+
+struct GemmParams {
+    int M, N, K;
+    const int8_t* A; long lda;
+    const int8_t* W; long ldw;
+    int inner_count;
+    long a_outer, a_inner, w_outer, w_inner, o_outer, o_inner;
+    const float* bias;
+    const float* alpha_vec;
+    float alpha;
+    const int8_t* resid;
+    float resid_scale;
+    int has_table;
+    DevTable table;
+    float out_inv_scale;
+    const float* out_inv_scale_vec;
+    int split_cols;
+    float inv3[3];
+    long ldo;
+    int vec_out;
+    int8_t* out_q;
+    float* out_f32;
+    int32_t* out_acc;
+    uint16_t* dbg_seg;
+    int tiles_m, tiles_n;
+};
+
+// XOR swizzle of the 16-byte chunk index inside a 64-byte LDS row: rows that fall into the same
+// bank window get different chunk positions, for both a 128-byte and a 256-byte wide LDS port.
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 2) & 3); }
+
+__device__ __forceinline__ int lds_off(int row, int chunk) { return row * kBK + ((chunk ^ swz(row)) << 4); }
+
+// 16 bytes of a row-major int8 matrix at (row, k .. k+15); zeros outside [0,nrows) x [0,K).
+template <bool kAligned>
+__device__ __forceinline__ v4i load_chunk(const int8_t* __restrict__ X, long ld, int row, int nrows,
+                                          int k, int K)
+{
+    v4i v = {0, 0, 0, 0};
+    if (row < nrows) {
+        const int8_t* p = X + (long)row * ld + k;
+        if (kAligned) {
+            if (k < K) v = *reinterpret_cast<const v4i*>(p);
+        } else {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                unsigned word = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    if (k + 4 * w + b < K) word |= (unsigned)(uint8_t)p[4 * w + b] << (8 * b);
+                v[w] = (int)word;
+            }
+        }
+    }
+    return v;
+}
+
+template <int BM, int BN, int WM, int WN, bool kAligned, bool kWKN>
+__global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
+{
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int WAVES_N = BN / WN;
+    static_assert((BM / WM) * (BN / WN) == kGemmThreads / 64, "four wavefronts per workgroup");
+    constexpr int LA = BM / 64, LW = BN / 64;  // 16-byte chunks per thread and stage
+
+    __shared__ __attribute__((aligned(16))) int8_t sA[2][BM * kBK];
+    __shared__ __attribute__((aligned(16))) int8_t sW[2][BN * kBK];
+    extern __shared__ float2 s_kb[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wave_m = (wave / WAVES_N) * WM;
+    const int wave_n = (wave % WAVES_N) * WN;
+
+    const int tile_m = blockIdx.x % p.tiles_m;
+    const int tile_n = blockIdx.x / p.tiles_m;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int outer = blockIdx.y / p.inner_count;
+    const int inner = blockIdx.y % p.inner_count;
+    const int8_t* __restrict__ A = p.A + outer * p.a_outer + inner * p.a_inner;
+    const int8_t* __restrict__ W = p.W + outer * p.w_outer + inner * p.w_inner;
+    const long obase = outer * p.o_outer + inner * p.o_inner;
+
+    if (p.has_table) stage_table(s_kb, p.table);
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    v4i ra[LA], rw[LW];
+    const int ld_row = tid >> 2, ld_chunk = tid & 3;
+
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i)
+            ra[i] = load_chunk<kAligned>(A, p.lda, m0 + ld_row + 64 * i, p.M, k0 + 16 * ld_chunk, p.K);
+        if (!kWKN) {
+#pragma unroll
+            for (int i = 0; i < LW; ++i)
+                rw[i] = load_chunk<kAligned>(W, p.ldw, n0 + ld_row + 64 * i, p.N, k0 + 16 * ld_chunk, p.K);
+        } else {
+            // W is [K, N]: this thread takes k-row kk and 16 consecutive n
+#pragma unroll
+            for (int i = 0; i < LW; ++i) {
+                const int idx = tid + kGemmThreads * i;  // 0 .. 64 * BN/16 - 1
+                const int kk = idx / (BN / 16), nc = idx % (BN / 16);
+                rw[i] = load_chunk<kAligned>(W, p.ldw, k0 + kk, p.K, n0 + 16 * nc, p.N);
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i)
+            *reinterpret_cast<v4i*>(&sA[buf][lds_off(ld_row + 64 * i, ld_chunk)]) = ra[i];
+        if (!kWKN) {
+#pragma unroll
+            for (int i = 0; i < LW; ++i)
+                *reinterpret_cast<v4i*>(&sW[buf][lds_off(ld_row + 64 * i, ld_chunk)]) = rw[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < LW; ++i) {
+                const int idx = tid + kGemmThreads * i;
+                const int kk = idx / (BN / 16), nc = idx % (BN / 16);
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {
+                    const int n = 16 * nc + b;
+                    sW[buf][lds_off(n, kk >> 4) + (kk & 15)] = (int8_t)((unsigned)rw[i][b >> 2] >> (8 * (b & 3)));
+                }
+            }
+        }
+    };
+
+    const int nk = (p.K + kBK - 1) / kBK;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) fetch((kt + 1) * kBK);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i fa[TM], fw[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const v4i*>(&sA[cur][lds_off(wave_m + 32 * i + frag_row, 2 * ks + frag_half)]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fw[j] = *reinterpret_cast<const v4i*>(&sW[cur][lds_off(wave_n + 32 * j + frag_row, 2 * ks + frag_half)]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) stash(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane owns row m; registers 4g .. 4g+3 are columns nb .. nb+3 ----------------
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wave_m + 32 * i + frag_row;
+        if (m >= p.M) continue;
+        const long rowoff = obase + (long)m * p.ldo;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int nb = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
+                if (nb >= p.N) continue;
+                const bool full = nb + 3 < p.N;
+                int a4[4], q4[4], s4[4];
+                float y4[4];
+                unsigned res_word = 0;
+                const bool vec = p.vec_out && full;
+                if (p.resid && vec) res_word = *reinterpret_cast<const unsigned*>(p.resid + rowoff + nb);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int n = nb + e;
+                    a4[e] = acc[i][j][4 * g + e];
+                    y4[e] = 0.0f; q4[e] = 0; s4[e] = 0;
+                    if (n < p.N) {
+                        const float scale = p.alpha_vec ? p.alpha_vec[n] : p.alpha;
+                        float v = __builtin_fmaf((float)a4[e], scale, p.bias ? p.bias[n] : 0.0f);
+                        if (p.resid) {
+                            const int r = vec ? (int)(int8_t)(res_word >> (8 * e)) : (int)p.resid[rowoff + n];
+                            v = __builtin_fmaf((float)r, p.resid_scale, v);
+                        }
+                        if (p.has_table) v = pwl_eval(v, p.table, s_kb, s4[e]);
+                        y4[e] = v;
+                        float inv = p.out_inv_scale;
+                        if (p.out_inv_scale_vec) inv = p.out_inv_scale_vec[n];
+                        else if (p.split_cols > 0) inv = p.inv3[min(n / p.split_cols, 2)];
+                        q4[e] = requant(v, inv);
+                    }
+                }
+                if (vec) {
+                    if (p.out_q) *reinterpret_cast<unsigned*>(p.out_q + rowoff + nb) = pack4(q4[0], q4[1], q4[2], q4[3]);
+                    if (p.out_f32) *reinterpret_cast<v4f*>(p.out_f32 + rowoff + nb) = v4f{y4[0], y4[1], y4[2], y4[3]};
+                    if (p.out_acc) *reinterpret_cast<v4i*>(p.out_acc + rowoff + nb) = v4i{a4[0], a4[1], a4[2], a4[3]};
+                    if (p.dbg_seg && p.has_table)
+                        *reinterpret_cast<uint2*>(p.dbg_seg + rowoff + nb) =
+                            make_uint2((unsigned)s4[0] | ((unsigned)s4[1] << 16), (unsigned)s4[2] | ((unsigned)s4[3] << 16));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (nb + e < p.N) {
+                            if (p.out_q) p.out_q[rowoff + nb + e] = (int8_t)q4[e];
+                            if (p.out_f32) p.out_f32[rowoff + nb + e] = y4[e];
+                            if (p.out_acc) p.out_acc[rowoff + nb + e] = a4[e];
+                            if (p.dbg_seg && p.has_table) p.dbg_seg[rowoff + nb + e] = (uint16_t)s4[e];
+                        }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+static void launch_cfg(const GemmParams& p, bool al, bool wkn, dim3 grid, size_t shmem, hipStream_t s)
+{
+    if (al && !wkn) hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, true, false>), grid, dim3(kGemmThreads), shmem, s, p);
+    else if (!al && !wkn) hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, false, false>), grid, dim3(kGemmThreads), shmem, s, p);
+    else if (al && wkn) hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, true, true>), grid, dim3(kGemmThreads), shmem, s, p);
+    else hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, false, true>), grid, dim3(kGemmThreads), shmem, s, p);
+}
+
+int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
+{
+    if (g.M == 0) return NM_OK;
+    GemmParams p{};
+    p.M = g.M; p.N = g.N; p.K = g.K;
+    p.A = g.A; p.lda = g.lda; p.W = g.W; p.ldw = g.ldw;
+    p.inner_count = g.inner_count;
+    p.a_outer = g.a_outer; p.a_inner = g.a_inner; p.w_outer = g.w_outer; p.w_inner = g.w_inner;
+    p.o_outer = g.o_outer; p.o_inner = g.o_inner;
+    p.bias = g.bias; p.alpha_vec = g.alpha_vec; p.alpha = g.alpha;
+    p.resid = g.resid; p.resid_scale = g.resid_scale;
+    p.has_table = g.has_table; p.table = g.table;
+    p.out_inv_scale = g.out_inv_scale; p.out_inv_scale_vec = g.out_inv_scale_vec;
+    p.split_cols = g.split_cols;
+    for (int i = 0; i < 3; ++i) p.inv3[i] = g.inv3[i];
+    p.ldo = g.ldo;
+    p.out_q = g.out_q; p.out_f32 = g.out_f32; p.out_acc = g.out_acc; p.dbg_seg = g.dbg_seg;
+
+    // 16-byte loads need every row start and every batch offset on a 16-byte boundary
+    const bool a_al = aligned(g.A, 16) && g.lda % 16 == 0 && g.a_outer % 16 == 0 && g.a_inner % 16 == 0;
+    const bool w_al = aligned(g.W, 16) && g.ldw % 16 == 0 && g.w_outer % 16 == 0 && g.w_inner % 16 == 0;
+    const bool al = a_al && w_al && g.K % 16 == 0 && (!g.w_is_kn || g.N % 16 == 0);
+    p.vec_out = g.ldo % 4 == 0 && g.o_outer % 4 == 0 && g.o_inner % 4 == 0 &&
+                (!g.out_q || aligned(g.out_q, 4)) && (!g.out_f32 || aligned(g.out_f32, 16)) &&
+                (!g.out_acc || aligned(g.out_acc, 16)) && (!g.dbg_seg || aligned(g.dbg_seg, 8)) &&
+                (!g.resid || aligned(g.resid, 4));
+
+    const size_t shmem = g.has_table ? sizeof(float2) * (size_t)g.table.nseg : 0;
+    const int batches = g.outer_count * g.inner_count;
+    if (batches > 65535) return fail(NM_ERR_UNSUPPORTED, "gemm: more than 65535 batched problems");
+    if (g.N <= 64) {
+        p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 63) / 64;
+        launch_cfg<128, 64, 32, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), shmem, stream);
+    } else {
+        p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 127) / 128;
+        launch_cfg<128, 128, 64, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), shmem, stream);
+    }
+    return check_hip(hipGetLastError(), "gemm launch");
+}
+
+}  // namespace nm
+
+using namespace nm;
+
+extern "C" {
+
+int32_t nm_gemm_pwl(const nm_gemm_desc* d, void* stream)
+{
+    if (!d) return fail(NM_ERR_INVALID_ARG, "nm_gemm_pwl: desc is NULL");
+    if (d->M < 1 || d->N < 1 || d->K < 1) return fail(NM_ERR_INVALID_ARG, "nm_gemm_pwl: M, N, K must be >= 1");
+    if (!d->A || !d->W) return fail(NM_ERR_INVALID_ARG, "nm_gemm_pwl: A or W is NULL");
+    if (!d->out_q && !d->out_f32 && !d->out_acc) return fail(NM_ERR_INVALID_ARG, "nm_gemm_pwl: no output");
+    if (d->K > 65536) return fail(NM_ERR_UNSUPPORTED, "nm_gemm_pwl: K %d > 65536", d->K);
+    if ((int64_t)d->M * d->N >= (1LL << 31)) return fail(NM_ERR_UNSUPPORTED, "nm_gemm_pwl: M*N >= 2^31");
+    GemmArgs g;
+    g.M = d->M; g.N = d->N; g.K = d->K;
+    g.A = d->A; g.lda = d->K; g.W = d->W; g.ldw = d->K;
+    g.bias = d->bias; g.alpha_vec = d->alpha_vec; g.alpha = d->alpha;
+    g.resid = d->resid; g.resid_scale = d->resid_scale;
+    if (d->table_idx >= 0) {
+        int32_t rc = get_dev_table(d->tables, d->table_idx, &g.table, "nm_gemm_pwl");
+        if (rc) return rc;
+        g.has_table = 1;
+    }
+    g.out_inv_scale = d->out_inv_scale; g.out_inv_scale_vec = d->out_inv_scale_vec;
+    g.ldo = d->N;
+    g.out_q = d->out_q; g.out_f32 = d->out_f32; g.out_acc = d->out_acc; g.dbg_seg = d->dbg_seg;
+    return launch_gemm(g, (hipStream_t)stream);
+}
+
+static int32_t check_attn(const char* what, const void* a, const void* b, const void* c, int32_t B,
+                          int32_t S, int32_t H, int32_t heads)
+{
+    if (!a || !b || !c) return fail(NM_ERR_INVALID_ARG, "%s: NULL pointer", what);
+    if (B < 1 || S < 1 || H < 1 || heads < 1) return fail(NM_ERR_INVALID_ARG, "%s: dimensions must be >= 1", what);
+    if (H % heads != 0) return fail(NM_ERR_INVALID_ARG, "%s: H %d not divisible by heads %d", what, H, heads);
+    if (S > 4096) return fail(NM_ERR_UNSUPPORTED, "%s: S %d > 4096", what, S);
+    if ((int64_t)B * heads > 65535) return fail(NM_ERR_UNSUPPORTED, "%s: B * heads > 65535", what);
+    if ((int64_t)B * S * 3 * H >= (1LL << 31)) return fail(NM_ERR_UNSUPPORTED, "%s: B*S*3H >= 2^31", what);
+    return NM_OK;
+}
+
+int32_t nm_attn_scores(const int8_t* qkv, int32_t B, int32_t S, int32_t H, int32_t heads,
+                       int32_t* scores, void* stream)
+{
+    int32_t rc = check_attn("nm_attn_scores", qkv, qkv, scores, B, S, H, heads);
+    if (rc) return rc;
+    const int d = H / heads;
+    GemmArgs g;
+    g.M = S; g.N = S; g.K = d;
+    g.A = qkv; g.lda = 3L * H; g.W = qkv + H; g.ldw = 3L * H;
+    g.outer_count = B; g.inner_count = heads;
+    g.a_outer = (long)S * 3 * H; g.a_inner = d;
+    g.w_outer = (long)S * 3 * H; g.w_inner = d;
+    g.o_outer = (long)heads * S * S; g.o_inner = (long)S * S;
+    g.ldo = S;
+    g.out_acc = scores;
+    return launch_gemm(g, (hipStream_t)stream);
+}
+
+int32_t nm_attn_context(const int8_t* p, const int8_t* qkv, int32_t B, int32_t S, int32_t H,
+                        int32_t heads, float alpha, float out_inv_scale, int8_t* ctx, void* stream)
+{
+    int32_t rc = check_attn("nm_attn_context", p, qkv, ctx, B, S, H, heads);
+    if (rc) return rc;
+    const int d = H / heads;
+    GemmArgs g;
+    g.M = S; g.N = d; g.K = S;
+    g.A = p; g.lda = S;
+    g.W = qkv + 2L * H; g.ldw = 3L * H; g.w_is_kn = 1;  // V is [S, d] per head: k = j runs over rows
+    g.outer_count = B; g.inner_count = heads;
+    g.a_outer = (long)heads * S * S; g.a_inner = (long)S * S;
+    g.w_outer = (long)S * 3 * H; g.w_inner = d;
+    g.o_outer = (long)S * H; g.o_inner = d;
+    g.ldo = H;
+    g.alpha = alpha; g.out_inv_scale = out_inv_scale;
+    g.out_q = ctx;
+    return launch_gemm(g, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,158 @@
+// nm_encoder_layer: one post-LayerNorm transformer encoder layer as a fixed sequence of kernel
+// launches on one stream (paper Section 3: linear operators as matrix products, nonlinear
+// operators as PWL tables).  Host code only: it validates, carves the workspace and queues the
+// nine steps; nothing is allocated and the host never waits for the GPU.
+#include "nm_internal.h"
+
+namespace nm {
+
+static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct LayerPlan {
+    size_t off_qkv, off_scores, off_p, off_ctx, off_attn, off_ln1, off_ffn1, off_ffn2, total;
+};
+
+static LayerPlan plan_layer(const nm_layer_desc* d)
+{
+    const size_t M = (size_t)d->B * d->S, H = d->H, F = d->F;
+    const size_t SS = (size_t)d->B * d->heads * d->S * d->S;
+    LayerPlan p{};
+    size_t o = 0;
+    auto take = [&o](size_t bytes) { size_t at = o; o = round_up(o + bytes, 256); return at; };
+    p.off_qkv = take(M * 3 * H);
+    p.off_scores = take(SS * sizeof(int32_t));
+    p.off_p = take(SS);
+    p.off_ctx = take(M * H);
+    p.off_attn = take(M * H * sizeof(float));
+    p.off_ln1 = take(M * H);
+    p.off_ffn1 = take(M * F);
+    p.off_ffn2 = take(M * H * sizeof(float));
+    p.total = o;
+    return p;
+}
+
+static int32_t validate_layer(const nm_layer_desc* d, const char* what)
+{
+    if (!d) return fail(NM_ERR_INVALID_ARG, "%s: desc is NULL", what);
+    if (d->B < 1 || d->S < 1 || d->H < 1 || d->heads < 1 || d->F < 1)
+        return fail(NM_ERR_INVALID_ARG, "%s: dimensions must be >= 1", what);
+    if (d->H % d->heads != 0)
+        return fail(NM_ERR_INVALID_ARG, "%s: H %d not divisible by heads %d", what, d->H, d->heads);
+    if (d->S > 4096 || d->H > 4096)
+        return fail(NM_ERR_UNSUPPORTED, "%s: S and H must be <= 4096 (row kernels)", what);
+    if (d->F > 65536) return fail(NM_ERR_UNSUPPORTED, "%s: F > 65536", what);
+    if ((int64_t)d->B * d->heads > 65535) return fail(NM_ERR_UNSUPPORTED, "%s: B * heads > 65535", what);
+    const int64_t M = (int64_t)d->B * d->S;
+    if (M * 3 * d->H >= (1LL << 31) || M * d->F >= (1LL << 31))
+        return fail(NM_ERR_UNSUPPORTED, "%s: B*S*max(3H, F) >= 2^31", what);
+    return NM_OK;
+}
+
+}  // namespace nm
+
+using namespace nm;
+
+extern "C" {
+
+int32_t nm_encoder_layer_workspace(const nm_layer_desc* desc, size_t* bytes)
+{
+    int32_t rc = validate_layer(desc, "nm_encoder_layer_workspace");
+    if (rc) return rc;
+    if (!bytes) return fail(NM_ERR_INVALID_ARG, "nm_encoder_layer_workspace: bytes is NULL");
+    *bytes = plan_layer(desc).total;
+    return NM_OK;
+}
+
+int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, float* y_f32,
+                         void* ws, size_t ws_bytes, const nm_layer_taps* taps, void* stream_)
+{
+    int32_t rc = validate_layer(d, "nm_encoder_layer");
+    if (rc) return rc;
+    if (!x) return fail(NM_ERR_INVALID_ARG, "nm_encoder_layer: x is NULL");
+    if (!y_q && !y_f32) return fail(NM_ERR_INVALID_ARG, "nm_encoder_layer: no output");
+    if (!d->Wqkv || !d->Wo || !d->W1 || !d->W2 || !d->gamma1 || !d->beta1 || !d->gamma2 || !d->beta2)
+        return fail(NM_ERR_INVALID_ARG, "nm_encoder_layer: NULL weight or LayerNorm vector");
+    DevTable t_gelu, t_exp, t_recip, t_rsqrt;
+    if ((rc = get_dev_table(d->tables, d->gelu_idx, &t_gelu, "nm_encoder_layer(gelu)"))) return rc;
+    if ((rc = get_dev_table(d->tables, d->exp_idx, &t_exp, "nm_encoder_layer(exp)"))) return rc;
+    if ((rc = get_dev_table(d->tables, d->recip_idx, &t_recip, "nm_encoder_layer(recip)"))) return rc;
+    if ((rc = get_dev_table(d->tables, d->rsqrt_idx, &t_rsqrt, "nm_encoder_layer(rsqrt)"))) return rc;
+    const LayerPlan plan = plan_layer(d);
+    if (!ws) return fail(NM_ERR_WORKSPACE, "nm_encoder_layer: workspace is NULL");
+    if (!aligned(ws, 256)) return fail(NM_ERR_WORKSPACE, "nm_encoder_layer: workspace not 256-byte aligned");
+    if (ws_bytes < plan.total)
+        return fail(NM_ERR_WORKSPACE, "nm_encoder_layer: workspace %zu bytes < %zu needed", ws_bytes, plan.total);
+
+    hipStream_t stream = (hipStream_t)stream_;
+    char* w = static_cast<char*>(ws);
+    const int B = d->B, S = d->S, H = d->H, nh = d->heads, F = d->F;
+    const int M = B * S;
+    auto pick = [&](void* tap, size_t off) -> void* { return tap ? tap : (void*)(w + off); };
+    int8_t* qkv = (int8_t*)pick(taps ? taps->qkv : nullptr, plan.off_qkv);
+    int32_t* scores = (int32_t*)pick(taps ? taps->scores : nullptr, plan.off_scores);
+    int8_t* pm = (int8_t*)pick(taps ? taps->p : nullptr, plan.off_p);
+    int8_t* ctx = (int8_t*)pick(taps ? taps->ctx : nullptr, plan.off_ctx);
+    float* attn = (float*)pick(taps ? taps->attn : nullptr, plan.off_attn);
+    int8_t* ln1 = (int8_t*)pick(taps ? taps->ln1 : nullptr, plan.off_ln1);
+    int8_t* ffn1 = (int8_t*)pick(taps ? taps->ffn1 : nullptr, plan.off_ffn1);
+    float* ffn2 = (float*)pick(taps ? taps->ffn2 : nullptr, plan.off_ffn2);
+
+    // 1: QKV projection, three output scales by column third
+    {
+        GemmArgs g;
+        g.M = M; g.N = 3 * H; g.K = H;
+        g.A = x; g.lda = H; g.W = d->Wqkv; g.ldw = H;
+        g.bias = d->bqkv; g.alpha = d->alpha_qkv;
+        g.split_cols = H; g.inv3[0] = d->inv_s_q; g.inv3[1] = d->inv_s_k; g.inv3[2] = d->inv_s_v;
+        g.ldo = 3L * H; g.out_q = qkv;
+        if ((rc = launch_gemm(g, stream))) return rc;
+    }
+    // 2: scores = Q K^T per (batch, head)
+    if ((rc = nm_attn_scores(qkv, B, S, H, nh, scores, stream))) return rc;
+    // 3: softmax-PWL over every score row
+    if ((rc = launch_softmax(scores, NM_DT_I32, d->alpha_scores, (int64_t)B * nh * S, S, t_exp, t_recip,
+                             d->inv_s_p, pm, nullptr, nullptr, nullptr, stream)))
+        return rc;
+    // 4: context = P V per (batch, head)
+    if ((rc = nm_attn_context(pm, qkv, B, S, H, nh, d->alpha_ctx, d->inv_s_ctx, ctx, stream))) return rc;
+    // 5: output projection + bias + residual(x) -> fp32
+    {
+        GemmArgs g;
+        g.M = M; g.N = H; g.K = H;
+        g.A = ctx; g.lda = H; g.W = d->Wo; g.ldw = H;
+        g.bias = d->bo; g.alpha = d->alpha_o;
+        g.resid = x; g.resid_scale = d->resid1_scale;
+        g.ldo = H; g.out_f32 = attn;
+        if ((rc = launch_gemm(g, stream))) return rc;
+    }
+    // 6: LayerNorm-PWL -> int8
+    if ((rc = launch_layernorm(attn, d->gamma1, d->beta1, d->eps1, M, H, t_rsqrt, d->inv_s_ln1, ln1,
+                               nullptr, nullptr, stream)))
+        return rc;
+    // 7: FFN1 + bias, GELU-PWL in the epilogue -> int8
+    {
+        GemmArgs g;
+        g.M = M; g.N = F; g.K = H;
+        g.A = ln1; g.lda = H; g.W = d->W1; g.ldw = H;
+        g.bias = d->b1; g.alpha = d->alpha_1;
+        g.has_table = 1; g.table = t_gelu;
+        g.out_inv_scale = d->inv_s_ffn1;
+        g.ldo = F; g.out_q = ffn1;
+        if ((rc = launch_gemm(g, stream))) return rc;
+    }
+    // 8: FFN2 + bias + residual(LN1 output) -> fp32
+    {
+        GemmArgs g;
+        g.M = M; g.N = H; g.K = F;
+        g.A = ffn1; g.lda = F; g.W = d->W2; g.ldw = F;
+        g.bias = d->b2; g.alpha = d->alpha_2;
+        g.resid = ln1; g.resid_scale = d->resid2_scale;
+        g.ldo = H; g.out_f32 = ffn2;
+        if ((rc = launch_gemm(g, stream))) return rc;
+    }
+    // 9: LayerNorm-PWL -> layer output
+    return launch_layernorm(ffn2, d->gamma2, d->beta2, d->eps2, M, H, t_rsqrt, d->inv_s_out, y_q, y_f32,
+                            nullptr, stream);
+}
+
+}  // extern "C"

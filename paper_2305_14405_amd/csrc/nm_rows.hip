@@ -1,0 +1,482 @@
+// Row-wise and element-wise PWL kernels for gfx950: stand-alone PWL, softmax-PWL, LayerNorm-PWL.
+//
+// These kernels are bound by HBM bandwidth (5 bytes per element: a 4-byte input, a 1-byte code),
+// so their design is about memory access: each lane owns groups of four consecutive elements
+// (one 16-byte load, one packed 4-byte int8 store), a row is held entirely in registers between
+// its reductions (read once, written once), sub-wavefront rows share a wavefront so short rows
+// still issue full-width memory instructions, and the {k, b} table of the per-element function
+// sits in LDS.
+//
+// Row sums use the library's normative order: element j goes to accumulator (j / 4) % 64, each
+// accumulator adds in increasing j from +0, and the partial sums are combined by a butterfly with
+// partner masks 32, 16, 8, 4, 2, 1.  A row of at most 4*G elements (G a power of two below 64)
+// only has G non-zero accumulators; adding the +0 of an empty accumulator changes nothing, so a
+// butterfly over the G lanes that own the row gives the same bits.
+#include "nm_device.h"
+
+namespace nm {
+
+constexpr int kRowThreads = 256;
+
+template <typename T>
+__device__ __forceinline__ T shfl_xor(T v, int mask)
+{
+    return __shfl_xor(v, mask, 64);
+}
+
+template <int G>
+__device__ __forceinline__ float group_sum(float v)
+{
+#pragma unroll
+    for (int mask = G / 2; mask >= 1; mask >>= 1) v = v + shfl_xor(v, mask);
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Stand-alone element-wise PWL (the non-fused element-wise path).
+// ------------------------------------------------------------------------------------------
+template <bool kVec>
+__global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
+    const void* __restrict__ in, int in_is_i32, float alpha, long n, DevTable t,
+    float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
+    uint16_t* __restrict__ dbg_seg)
+{
+    extern __shared__ float2 s_kb[];
+    stage_table(s_kb, t);
+    __syncthreads();
+    const long nthreads = (long)gridDim.x * blockDim.x;
+    const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (kVec) {
+        const long ngroups = n / 4;
+        for (long gidx = tid; gidx < ngroups; gidx += nthreads) {
+            float x[4];
+            if (in_is_i32) {
+                v4i a = reinterpret_cast<const v4i*>(in)[gidx];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = (float)a[e] * alpha;
+            } else {
+                v4f a = reinterpret_cast<const v4f*>(in)[gidx];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = a[e] * alpha;
+            }
+            float y[4];
+            int s[4], q[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                y[e] = pwl_eval(x[e], t, s_kb, s[e]);
+                q[e] = requant(y[e], out_inv_scale);
+            }
+            if (out_f32) reinterpret_cast<v4f*>(out_f32)[gidx] = v4f{y[0], y[1], y[2], y[3]};
+            if (out_q) reinterpret_cast<unsigned*>(out_q)[gidx] = pack4(q[0], q[1], q[2], q[3]);
+            if (dbg_seg)
+                reinterpret_cast<uint2*>(dbg_seg)[gidx] =
+                    make_uint2((unsigned)s[0] | ((unsigned)s[1] << 16),
+                               (unsigned)s[2] | ((unsigned)s[3] << 16));
+        }
+    }
+    // scalar path: everything when !kVec, the (< 4 element) tail otherwise
+    const long first = kVec ? (n / 4) * 4 : 0;
+    for (long i = first + tid; i < n; i += nthreads) {
+        float x = in_is_i32 ? (float)reinterpret_cast<const int*>(in)[i] * alpha
+                            : reinterpret_cast<const float*>(in)[i] * alpha;
+        int s;
+        float y = pwl_eval(x, t, s_kb, s);
+        if (out_f32) out_f32[i] = y;
+        if (out_q) out_q[i] = (int8_t)requant(y, out_inv_scale);
+        if (dbg_seg) dbg_seg[i] = (uint16_t)s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Softmax-PWL.  G lanes own a row (G = 64 for rows longer than 128 elements); a lane owns the
+// 4-element groups g, g + G, ... (C of them).
+// ------------------------------------------------------------------------------------------
+template <int G, int C, bool kI32, bool kVec>
+__global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
+    const void* __restrict__ in, float alpha, long rows, int cols, DevTable t_exp, DevTable t_recip,
+    float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
+    uint16_t* __restrict__ seg_exp, uint16_t* __restrict__ seg_recip)
+{
+    extern __shared__ float2 s_kb[];
+    stage_table(s_kb, t_exp);
+    __syncthreads();
+    constexpr int kRowsPerWave = 64 / G;
+    constexpr int kRowsPerBlock = kRowsPerWave * (kRowThreads / 64);
+    const int lane = threadIdx.x & 63;
+    const int g = lane % G;
+    const int sub = (threadIdx.x >> 6) * kRowsPerWave + lane / G;
+
+    for (long row0 = (long)blockIdx.x * kRowsPerBlock; row0 < rows;
+         row0 += (long)gridDim.x * kRowsPerBlock) {
+        const long row = row0 + sub;
+        const bool live = row < rows;
+        const long base = row * (long)cols;
+        float e[C][4];
+        bool ok[C][4];
+        int ai[C][4];
+        // ---- load + row maximum -------------------------------------------------------------
+        int mi = INT_MIN;
+        float mf = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int j0 = 4 * (g + G * c);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) ok[c][q] = live && (j0 + q) < cols;
+            if (kVec) {
+                if (ok[c][0]) {  // cols % 4 == 0: a group is all in or all out
+                    if (kI32) {
+                        v4i a = *reinterpret_cast<const v4i*>(reinterpret_cast<const int*>(in) + base + j0);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) ai[c][q] = a[q];
+                    } else {
+                        v4f a = *reinterpret_cast<const v4f*>(reinterpret_cast<const float*>(in) + base + j0);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) e[c][q] = a[q];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (ok[c][q]) {
+                        if (kI32) ai[c][q] = reinterpret_cast<const int*>(in)[base + j0 + q];
+                        else e[c][q] = reinterpret_cast<const float*>(in)[base + j0 + q];
+                    }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (ok[c][q]) {
+                    if (kI32) mi = max(mi, ai[c][q]);
+                    else mf = __builtin_fmaxf(mf, e[c][q]);
+                }
+        }
+#pragma unroll
+        for (int mask = G / 2; mask >= 1; mask >>= 1) {
+            if (kI32) mi = max(mi, shfl_xor(mi, mask));
+            else mf = __builtin_fmaxf(mf, shfl_xor(mf, mask));
+        }
+        // ---- exp + canonical sum ------------------------------------------------------------
+        float part = 0.0f;
+        int se[C][4];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (ok[c][q]) {
+                    float tt = kI32 ? (float)(ai[c][q] - mi) * alpha : (e[c][q] - mf) * alpha;
+                    e[c][q] = pwl_eval(tt, t_exp, s_kb, se[c][q]);
+                    part = part + e[c][q];
+                } else {
+                    e[c][q] = 0.0f;
+                    se[c][q] = 0;
+                }
+            }
+        }
+        const float S = group_sum<G>(part);
+        int sr;
+        const float r = pwl_eval(S, t_recip, t_recip.kb, sr);
+        if (seg_recip && live && g == 0) seg_recip[row] = (uint16_t)sr;
+        // ---- scale + store -------------------------------------------------------------------
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int j0 = 4 * (g + G * c);
+            float p[4];
+            int qv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                p[q] = e[c][q] * r;
+                qv[q] = requant(p[q], out_inv_scale);
+            }
+            if (kVec) {
+                if (ok[c][0]) {
+                    if (out_f32) *reinterpret_cast<v4f*>(out_f32 + base + j0) = v4f{p[0], p[1], p[2], p[3]};
+                    if (out_q) *reinterpret_cast<unsigned*>(out_q + base + j0) = pack4(qv[0], qv[1], qv[2], qv[3]);
+                    if (seg_exp)
+                        *reinterpret_cast<uint2*>(seg_exp + base + j0) =
+                            make_uint2((unsigned)se[c][0] | ((unsigned)se[c][1] << 16),
+                                       (unsigned)se[c][2] | ((unsigned)se[c][3] << 16));
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (ok[c][q]) {
+                        if (out_f32) out_f32[base + j0 + q] = p[q];
+                        if (out_q) out_q[base + j0 + q] = (int8_t)qv[q];
+                        if (seg_exp) seg_exp[base + j0 + q] = (uint16_t)se[c][q];
+                    }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// LayerNorm-PWL.  Same ownership as softmax.
+// ------------------------------------------------------------------------------------------
+template <int G, int C, bool kVec>
+__global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
+    const float* __restrict__ in, const float* __restrict__ gamma, const float* __restrict__ beta,
+    float eps, float inv_L, long rows, int cols, DevTable t, float out_inv_scale,
+    int8_t* __restrict__ out_q, float* __restrict__ out_f32, uint16_t* __restrict__ seg)
+{
+    constexpr int kRowsPerWave = 64 / G;
+    constexpr int kRowsPerBlock = kRowsPerWave * (kRowThreads / 64);
+    const int lane = threadIdx.x & 63;
+    const int g = lane % G;
+    const int sub = (threadIdx.x >> 6) * kRowsPerWave + lane / G;
+
+    for (long row0 = (long)blockIdx.x * kRowsPerBlock; row0 < rows;
+         row0 += (long)gridDim.x * kRowsPerBlock) {
+        const long row = row0 + sub;
+        const bool live = row < rows;
+        const long base = row * (long)cols;
+        float x[C][4];
+        bool ok[C][4];
+        float part = 0.0f;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int j0 = 4 * (g + G * c);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                ok[c][q] = live && (j0 + q) < cols;
+                x[c][q] = 0.0f;
+            }
+            if (kVec) {
+                if (ok[c][0]) {
+                    v4f a = *reinterpret_cast<const v4f*>(in + base + j0);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) x[c][q] = a[q];
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (ok[c][q]) x[c][q] = in[base + j0 + q];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (ok[c][q]) part = part + x[c][q];
+        }
+        const float mu = group_sum<G>(part) * inv_L;
+        float part2 = 0.0f;
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (ok[c][q]) {
+                    x[c][q] = x[c][q] - mu;
+                    part2 = __builtin_fmaf(x[c][q], x[c][q], part2);
+                }
+        const float var = group_sum<G>(part2) * inv_L;
+        const float u = var + eps;
+        int sr;
+        const float r = pwl_eval(u, t, t.kb, sr);
+        if (seg && live && g == 0) seg[row] = (uint16_t)sr;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int j0 = 4 * (g + G * c);
+            float y[4];
+            int qv[4];
+            if (kVec) {
+                if (ok[c][0]) {
+                    v4f ga = *reinterpret_cast<const v4f*>(gamma + j0);
+                    v4f be = *reinterpret_cast<const v4f*>(beta + j0);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        y[q] = __builtin_fmaf(x[c][q] * r, ga[q], be[q]);
+                        qv[q] = requant(y[q], out_inv_scale);
+                    }
+                    if (out_f32) *reinterpret_cast<v4f*>(out_f32 + base + j0) = v4f{y[0], y[1], y[2], y[3]};
+                    if (out_q) *reinterpret_cast<unsigned*>(out_q + base + j0) = pack4(qv[0], qv[1], qv[2], qv[3]);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (ok[c][q]) {
+                        float yy = __builtin_fmaf(x[c][q] * r, gamma[j0 + q], beta[j0 + q]);
+                        if (out_f32) out_f32[base + j0 + q] = yy;
+                        if (out_q) out_q[base + j0 + q] = (int8_t)requant(yy, out_inv_scale);
+                    }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Host launchers
+// ------------------------------------------------------------------------------------------
+
+static int blocks_for(long units, int per_block)
+{
+    long b = (units + per_block - 1) / per_block;
+    const long cap = 256L * 16;  // 256 compute units, several resident blocks each
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+// Pick (G, C) so that G * 4 * C >= cols: G lanes per row, C groups per lane.
+struct RowShape { int G, C; };
+static RowShape row_shape(int cols)
+{
+    int groups = (cols + 3) / 4;
+    int G = 1;
+    while (G < 64 && G < groups) G *= 2;
+    int C = (groups + G - 1) / G;
+    static const int allowed[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    for (int a : allowed)
+        if (a >= C) return {G, a};
+    return {G, -1};
+}
+
+template <bool kI32, bool kVec>
+static bool launch_softmax_t(RowShape rs, dim3 grid_hint, size_t shmem, hipStream_t stream,
+                             const void* in, float alpha, long rows, int cols, const DevTable& te,
+                             const DevTable& tr, float ois, int8_t* oq, float* of, uint16_t* se,
+                             uint16_t* sr)
+{
+    (void)grid_hint;
+#define NM_SM_CASE(GG, CC)                                                                          \
+    if (rs.G == GG && rs.C == CC) {                                                                 \
+        constexpr int rpb = (64 / GG) * (kRowThreads / 64);                                         \
+        hipLaunchKernelGGL((softmax_pwl_kernel<GG, CC, kI32, kVec>), dim3(blocks_for(rows, rpb)),   \
+                           dim3(kRowThreads), shmem, stream, in, alpha, rows, cols, te, tr, ois, oq, \
+                           of, se, sr);                                                             \
+        return true;                                                                                \
+    }
+    NM_SM_CASE(1, 1) NM_SM_CASE(2, 1) NM_SM_CASE(4, 1) NM_SM_CASE(8, 1) NM_SM_CASE(16, 1)
+    NM_SM_CASE(32, 1) NM_SM_CASE(64, 1) NM_SM_CASE(64, 2) NM_SM_CASE(64, 3) NM_SM_CASE(64, 4)
+    NM_SM_CASE(64, 6) NM_SM_CASE(64, 8) NM_SM_CASE(64, 12) NM_SM_CASE(64, 16)
+#undef NM_SM_CASE
+    return false;
+}
+
+int32_t launch_softmax(const void* in, int32_t in_dtype, float alpha, int64_t rows, int32_t cols,
+                       const DevTable& t_exp, const DevTable& t_recip, float out_inv_scale,
+                       int8_t* out_q, float* out_f32, uint16_t* seg_exp, uint16_t* seg_recip,
+                       hipStream_t stream)
+{
+    if (rows == 0) return NM_OK;
+    RowShape rs = row_shape(cols);
+    if (rs.C < 0) return fail(NM_ERR_UNSUPPORTED, "softmax: cols %d not supported", cols);
+    const bool vec = cols % 4 == 0 && aligned(in, 16) && (!out_f32 || aligned(out_f32, 16)) &&
+                     (!out_q || aligned(out_q, 4)) && (!seg_exp || aligned(seg_exp, 8));
+    const size_t shmem = sizeof(float2) * (size_t)t_exp.nseg;
+    bool ok;
+    const bool i32 = in_dtype == NM_DT_I32;
+    if (i32 && vec) ok = launch_softmax_t<true, true>(rs, dim3(), shmem, stream, in, alpha, rows, cols, t_exp, t_recip, out_inv_scale, out_q, out_f32, seg_exp, seg_recip);
+    else if (i32) ok = launch_softmax_t<true, false>(rs, dim3(), shmem, stream, in, alpha, rows, cols, t_exp, t_recip, out_inv_scale, out_q, out_f32, seg_exp, seg_recip);
+    else if (vec) ok = launch_softmax_t<false, true>(rs, dim3(), shmem, stream, in, alpha, rows, cols, t_exp, t_recip, out_inv_scale, out_q, out_f32, seg_exp, seg_recip);
+    else ok = launch_softmax_t<false, false>(rs, dim3(), shmem, stream, in, alpha, rows, cols, t_exp, t_recip, out_inv_scale, out_q, out_f32, seg_exp, seg_recip);
+    if (!ok) return fail(NM_ERR_UNSUPPORTED, "softmax: no kernel for cols %d", cols);
+    return check_hip(hipGetLastError(), "softmax launch");
+}
+
+template <bool kVec>
+static bool launch_layernorm_t(RowShape rs, hipStream_t stream, const float* in, const float* gamma,
+                               const float* beta, float eps, float inv_L, long rows, int cols,
+                               const DevTable& t, float ois, int8_t* oq, float* of, uint16_t* seg)
+{
+#define NM_LN_CASE(GG, CC)                                                                          \
+    if (rs.G == GG && rs.C == CC) {                                                                 \
+        constexpr int rpb = (64 / GG) * (kRowThreads / 64);                                         \
+        hipLaunchKernelGGL((layernorm_pwl_kernel<GG, CC, kVec>), dim3(blocks_for(rows, rpb)),       \
+                           dim3(kRowThreads), 0, stream, in, gamma, beta, eps, inv_L, rows, cols, t, \
+                           ois, oq, of, seg);                                                       \
+        return true;                                                                                \
+    }
+    NM_LN_CASE(1, 1) NM_LN_CASE(2, 1) NM_LN_CASE(4, 1) NM_LN_CASE(8, 1) NM_LN_CASE(16, 1)
+    NM_LN_CASE(32, 1) NM_LN_CASE(64, 1) NM_LN_CASE(64, 2) NM_LN_CASE(64, 3) NM_LN_CASE(64, 4)
+    NM_LN_CASE(64, 6) NM_LN_CASE(64, 8) NM_LN_CASE(64, 12) NM_LN_CASE(64, 16)
+#undef NM_LN_CASE
+    return false;
+}
+
+int32_t launch_layernorm(const float* in, const float* gamma, const float* beta, float eps,
+                         int64_t rows, int32_t cols, const DevTable& t, float out_inv_scale,
+                         int8_t* out_q, float* out_f32, uint16_t* seg, hipStream_t stream)
+{
+    if (rows == 0) return NM_OK;
+    RowShape rs = row_shape(cols);
+    if (rs.C < 0) return fail(NM_ERR_UNSUPPORTED, "layernorm: cols %d not supported", cols);
+    const float inv_L = (float)(1.0 / (double)cols);
+    const bool vec = cols % 4 == 0 && aligned(in, 16) && aligned(gamma, 16) && aligned(beta, 16) &&
+                     (!out_f32 || aligned(out_f32, 16)) && (!out_q || aligned(out_q, 4));
+    bool ok = vec ? launch_layernorm_t<true>(rs, stream, in, gamma, beta, eps, inv_L, rows, cols, t, out_inv_scale, out_q, out_f32, seg)
+                  : launch_layernorm_t<false>(rs, stream, in, gamma, beta, eps, inv_L, rows, cols, t, out_inv_scale, out_q, out_f32, seg);
+    if (!ok) return fail(NM_ERR_UNSUPPORTED, "layernorm: no kernel for cols %d", cols);
+    return check_hip(hipGetLastError(), "layernorm launch");
+}
+
+}  // namespace nm
+
+using namespace nm;
+
+extern "C" {
+
+int32_t nm_pwl_apply(const void* in, int32_t in_dtype, float alpha, int64_t n,
+                     const nm_tables* tables, int32_t idx, float out_inv_scale, int8_t* out_q,
+                     float* out_f32, uint16_t* dbg_seg, void* stream)
+{
+    if (in_dtype != NM_DT_I32 && in_dtype != NM_DT_F32)
+        return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: bad in_dtype %d", in_dtype);
+    if (n < 0) return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: n < 0");
+    DevTable t;
+    int32_t rc = get_dev_table(tables, idx, &t, "nm_pwl_apply");
+    if (rc) return rc;
+    if (n == 0) return NM_OK;  // an empty buffer may be a NULL pointer
+    if (!in) return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: in is NULL");
+    if (!out_q && !out_f32 && !dbg_seg) return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: no output");
+    const bool vec = aligned(in, 16) && (!out_f32 || aligned(out_f32, 16)) &&
+                     (!out_q || aligned(out_q, 4)) && (!dbg_seg || aligned(dbg_seg, 8));
+    const size_t shmem = sizeof(float2) * (size_t)t.nseg;
+    const int blocks = blocks_for(vec ? (n + 3) / 4 : n, kRowThreads);
+    if (vec)
+        hipLaunchKernelGGL(pwl_apply_kernel<true>, dim3(blocks), dim3(kRowThreads), shmem,
+                           (hipStream_t)stream, in, in_dtype == NM_DT_I32, alpha, (long)n, t,
+                           out_inv_scale, out_q, out_f32, dbg_seg);
+    else
+        hipLaunchKernelGGL(pwl_apply_kernel<false>, dim3(blocks), dim3(kRowThreads), shmem,
+                           (hipStream_t)stream, in, in_dtype == NM_DT_I32, alpha, (long)n, t,
+                           out_inv_scale, out_q, out_f32, dbg_seg);
+    return check_hip(hipGetLastError(), "nm_pwl_apply launch");
+}
+
+int32_t nm_softmax_pwl(const void* in, int32_t in_dtype, float alpha, int64_t rows, int32_t cols,
+                       const nm_tables* tables, int32_t exp_idx, int32_t recip_idx,
+                       float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* dbg_seg_exp,
+                       uint16_t* dbg_seg_recip, void* stream)
+{
+    if (in_dtype != NM_DT_I32 && in_dtype != NM_DT_F32)
+        return fail(NM_ERR_INVALID_ARG, "nm_softmax_pwl: bad in_dtype %d", in_dtype);
+    if (rows < 0 || cols < 1) return fail(NM_ERR_INVALID_ARG, "nm_softmax_pwl: bad shape");
+    if (cols > 4096) return fail(NM_ERR_UNSUPPORTED, "nm_softmax_pwl: cols %d > 4096", cols);
+    if (rows > (1LL << 40) / cols) return fail(NM_ERR_UNSUPPORTED, "nm_softmax_pwl: too many elements");
+    DevTable te, tr;
+    int32_t rc = get_dev_table(tables, exp_idx, &te, "nm_softmax_pwl(exp)");
+    if (rc) return rc;
+    rc = get_dev_table(tables, recip_idx, &tr, "nm_softmax_pwl(recip)");
+    if (rc) return rc;
+    if (rows == 0) return NM_OK;  // an empty matrix may be a NULL pointer
+    if (!in) return fail(NM_ERR_INVALID_ARG, "nm_softmax_pwl: in is NULL");
+    if (!out_q && !out_f32) return fail(NM_ERR_INVALID_ARG, "nm_softmax_pwl: no output");
+    return launch_softmax(in, in_dtype, alpha, rows, cols, te, tr, out_inv_scale, out_q, out_f32,
+                          dbg_seg_exp, dbg_seg_recip, (hipStream_t)stream);
+}
+
+int32_t nm_layernorm_pwl(const float* in, const float* gamma, const float* beta, float eps,
+                         int64_t rows, int32_t cols, const nm_tables* tables, int32_t rsqrt_idx,
+                         float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* dbg_seg,
+                         void* stream)
+{
+    if (rows < 0 || cols < 1) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl: bad shape");
+    if (cols > 4096) return fail(NM_ERR_UNSUPPORTED, "nm_layernorm_pwl: cols %d > 4096", cols);
+    if (!gamma || !beta) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl: gamma or beta is NULL");
+    DevTable t;
+    int32_t rc = get_dev_table(tables, rsqrt_idx, &t, "nm_layernorm_pwl");
+    if (rc) return rc;
+    if (rows == 0) return NM_OK;  // an empty matrix may be a NULL pointer
+    if (!in) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl: in is NULL");
+    if (!out_q && !out_f32) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl: no output");
+    return launch_layernorm(in, gamma, beta, eps, rows, cols, t, out_inv_scale, out_q, out_f32,
+                            dbg_seg, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, its host table
+builder agrees with the oracle's, and argument validation returns errors without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2305_14405_amd import binding as nm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return nm.load(preload_torch=False)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "nm.h")).read()
+    declared = set(re.findall(r"^(?:int32_t|void|const char\*)\s+(nm_[a-z_0-9]+)\(", header, re.M))
+    assert declared == set(nm.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.nm_version() >= 1000
+    assert nm.nm_last_error() is not None
+
+
+def test_no_torch_types_in_signatures():
+    header = open(os.path.join(ROOT, "include", "nm.h")).read()
+    assert "torch" not in header and "at::" not in header and 'extern "C"' in header
+
+
+FUNCS = ["gelu", "exp", "recip", "rsqrt", "sqrt", "relu", "identity"]
+RANGE = {"gelu": (-8.0, 8.0), "exp": (-16.0, 0.0), "recip": (1.0, 128.0), "rsqrt": (1e-3, 64.0),
+         "sqrt": (0.25, 64.0), "relu": (-8.0, 8.0), "identity": (-3.0, 5.0)}
+OID = {"gelu": 0, "exp": 1, "recip": 2, "rsqrt": 3, "relu": 4, "sqrt": 5, "identity": 6}
+
+
+def ulps(a, b):
+    a = np.asarray(a, np.float32)
+    b = np.asarray(b, np.float32)
+    return np.abs(a.astype(np.float64) - b.astype(np.float64)) / np.maximum(
+        np.spacing(np.maximum(np.abs(a), np.abs(b))).astype(np.float64), 1e-45)
+
+
+@pytest.mark.parametrize("name", FUNCS)
+@pytest.mark.parametrize("nseg", [1, 2, 64, 128, 1000])
+@pytest.mark.parametrize("flags", [0, nm.NM_TABLE_BIAS_CORRECT])
+def test_host_table_builder_matches_oracle(lib, oracle, name, nseg, flags):
+    lo, hi = RANGE[name]
+    k, b, inv_w, nd = nm.nm_table_build_host((name, lo, hi, nseg, flags))
+    t = oracle.build_table(OID[name], lo, hi, nseg, flags=oracle.FLAG_BIAS_CORRECT if flags else 0)
+    assert inv_w == t.inv_w
+    assert nd == nseg
+    # two independent binary64 evaluations rounded to fp32: equal up to the last bit, except where
+    # b is a tiny difference of large terms (GELU's tails), bounded absolutely instead
+    tol_abs = 4e-7 * max(abs(lo), abs(hi)) * np.maximum(np.abs(t.k), 1e-3)
+    assert np.all((ulps(k, t.k) <= 1) | (np.abs(k - t.k) <= 1e-9))
+    assert np.all((ulps(b, t.b) <= 1) | (np.abs(b - t.b) <= tol_abs))
+
+
+@pytest.mark.parametrize("name,dk", [("gelu", 0.1), ("exp", 0.05), ("recip", 0.02)])
+def test_host_merged_table_matches_oracle(lib, oracle, name, dk):
+    lo, hi = {"gelu": (-4.0, 4.0), "exp": (-8.0, 0.0), "recip": (1.0, 9.0)}[name]
+    nprim = 16
+    k, b, inv_w, nd = nm.nm_table_build_host((name, lo, hi, nprim, nm.NM_TABLE_MERGE, 0.0, dk))
+    t, n = oracle.build_table_merged(OID[name], lo, hi, nprim, dk)
+    assert nd == n
+    assert np.all(ulps(k, t.k) <= 1) and np.all((ulps(b, t.b) <= 1) | (np.abs(b - t.b) < 1e-6))
+    assert inv_w == t.inv_w
+
+
+def test_validation_errors_without_gpu(lib):
+    E = nm.NmError
+    for spec in [("exp", 0.0, 0.0, 8), ("exp", 0.0, 1.0, 0), (99, 0.0, 1.0, 8), ("recip", 0.0, 1.0, 8),
+                 ("rsqrt", -1.0, 1.0, 8)]:
+        with pytest.raises(E) as ei:
+            nm.nm_table_build_host(spec)
+        assert ei.value.status == nm.NM_ERR_INVALID_ARG
+    with pytest.raises(E) as ei:
+        nm.nm_table_build_host(("exp", 0.0, 1.0, 5000))
+    assert ei.value.status == nm.NM_ERR_UNSUPPORTED
+    assert "NM_MAX_SEGMENTS" in nm.nm_last_error()
+    # table objects: bad descriptors are rejected before any HIP call
+    with pytest.raises(E) as ei:
+        nm.nm_build_tables([("exp", 1.0, 0.0, 8)], stream=0)
+    assert ei.value.status == nm.NM_ERR_INVALID_ARG
+    with pytest.raises(E) as ei:
+        nm.nm_build_tables([("exp", -1.0, 0.0, 8)] * 17, stream=0)
+    assert ei.value.status == nm.NM_ERR_INVALID_ARG
+    assert nm.nm_tables_count(None) == 0
+    lib.nm_tables_destroy(None)  # null-safe
+
+
+def test_compute_entry_points_validate_before_launch(lib):
+    z = C.c_void_p(0)
+    one = C.c_void_p(256)  # a non-null dummy; never dereferenced because validation fails first
+    d = nm.GemmDesc()
+    assert lib.nm_gemm_pwl(None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_gemm_pwl(C.byref(d), z) == nm.NM_ERR_INVALID_ARG         # M = N = K = 0
+    d.M, d.N, d.K = 4, 4, 4
+    assert lib.nm_gemm_pwl(C.byref(d), z) == nm.NM_ERR_INVALID_ARG         # NULL operands
+    d.A, d.W = 256, 256
+    assert lib.nm_gemm_pwl(C.byref(d), z) == nm.NM_ERR_INVALID_ARG         # no output
+    d.out_q = 256
+    d.K = 70000
+    assert lib.nm_gemm_pwl(C.byref(d), z) == nm.NM_ERR_UNSUPPORTED
+    d.K = 4
+    d.table_idx = 0                                                          # table without tables
+    assert lib.nm_gemm_pwl(C.byref(d), z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_softmax_pwl(None, 0, 1.0, 1, 1, None, 0, 1, 1.0, one, None, None, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_softmax_pwl(one, 7, 1.0, 1, 1, None, 0, 1, 1.0, one, None, None, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_softmax_pwl(one, 0, 1.0, 1, 5000, None, 0, 1, 1.0, one, None, None, None, z) == nm.NM_ERR_UNSUPPORTED
+    assert lib.nm_softmax_pwl(one, 0, 1.0, 1, 8, None, 0, 1, 1.0, None, None, None, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_softmax_pwl(one, 0, 1.0, 1, 8, None, 0, 1, 1.0, one, None, None, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_layernorm_pwl(one, one, None, 1e-5, 1, 8, None, 0, 1.0, one, None, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_layernorm_pwl(one, one, one, 1e-5, 1, 0, None, 0, 1.0, one, None, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_pwl_apply(one, 0, 1.0, -1, None, 0, 1.0, one, None, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_attn_scores(one, 1, 8, 10, 3, one, z) == nm.NM_ERR_INVALID_ARG  # H % heads
+    assert lib.nm_attn_context(one, one, 1, 5000, 8, 1, 1.0, 1.0, one, z) == nm.NM_ERR_UNSUPPORTED
+    ld = nm.LayerDesc()
+    n = C.c_size_t()
+    assert lib.nm_encoder_layer_workspace(C.byref(ld), C.byref(n)) == nm.NM_ERR_INVALID_ARG
+    ld.B, ld.S, ld.H, ld.heads, ld.F = 32, 128, 768, 12, 3072
+    assert lib.nm_encoder_layer_workspace(C.byref(ld), C.byref(n)) == nm.NM_OK
+    M, H, F, SS = 4096, 768, 3072, 32 * 12 * 128 * 128
+    need = M * 3 * H + SS * 4 + SS + M * H + M * H * 4 + M * H + M * F + M * H * 4
+    assert need <= n.value <= need + 8 * 256
+    assert lib.nm_encoder_layer(C.byref(ld), one, one, None, one, n, None, z) == nm.NM_ERR_INVALID_ARG
+    ld.heads = 7
+    assert lib.nm_encoder_layer_workspace(C.byref(ld), C.byref(n)) == nm.NM_ERR_INVALID_ARG

@@ -1,0 +1,373 @@
+"""GPU parity: every C-ABI compute entry point against the CPU oracle, element by element, on the
+same seeded inputs (teacher forcing: each kernel is fed the oracle's inputs for that stage).
+
+Bar: int32 accumulators, segment indices and int8 codes bit-exact; fp32 values within 1e-5
+relative (the normative operation order makes them bit-reproducible in practice; the test also
+records how many differ at all)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2305_14405_amd import binding as nm
+from paper_2305_14405_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+OID = {"gelu": 0, "exp": 1, "recip": 2, "rsqrt": 3, "relu": 4, "sqrt": 5, "identity": 6}
+DEV = "cuda:0"
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def both_tables(oracle, specs, flags=0):
+    """Oracle tables and a device table object holding exactly the oracle's k, b."""
+    ot = [oracle.build_table(OID[f], lo, hi, n, flags=flags) for (f, lo, hi, n) in specs]
+    dt = nm.nm_tables_from_arrays([(f, lo, hi, n, flags) for (f, lo, hi, n) in specs],
+                                  [t.k for t in ot], [t.b for t in ot])
+    return ot, dt
+
+
+def assert_f32_close(got, want, what):
+    got = np.asarray(got)
+    want = np.asarray(want)
+    assert got.shape == want.shape
+    tol = 1e-5 * np.abs(want) + 1e-30
+    bad = ~((np.abs(got.astype(np.float64) - want.astype(np.float64)) <= tol) |
+            (np.isnan(got) & np.isnan(want)))
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} beyond 1e-5 relative"
+    nbits = int((got.view(np.uint32) != want.view(np.uint32)).sum())
+    print(f"[parity] {what}: fp32 within 1e-5 relative; {nbits} of {got.size} not bit-identical")
+
+
+def assert_exact(got, want, what):
+    got = np.asarray(got)
+    want = np.asarray(want)
+    assert got.shape == want.shape, what
+    n = int((got != want).sum())
+    assert n == 0, f"{what}: {n} of {got.size} differ"
+
+
+# ---- element-wise PWL -----------------------------------------------------------------------
+
+SPECS = [("gelu", -8.0, 8.0, 64), ("exp", -16.0, 0.0, 128), ("recip", 1.0, 64.0, 64),
+         ("rsqrt", 1e-3, 64.0, 37), ("relu", -8.0, 8.0, 2), ("gelu", -8.0, 8.0, 4096)]
+
+
+@pytest.mark.parametrize("ti", range(len(SPECS)))
+def test_pwl_apply_fp32_and_int32(oracle, ti):
+    ot, dt = both_tables(oracle, SPECS)
+    f, lo, hi, n = SPECS[ti]
+    x = W.sweep_values(lo, hi, 100003, seed=ti)
+    x = np.concatenate([x, np.array([np.nan, np.inf, -np.inf], np.float32)])
+    for inv in (1.0, 17.5):
+        y, q, s = oracle.pwl_apply(x, ot[ti], alpha=1.0, out_inv_scale=inv)
+        xd = dev(x)
+        yq, yf, ys = (torch.empty(x.size, dtype=torch.int8, device=DEV),
+                      torch.empty(x.size, dtype=torch.float32, device=DEV),
+                      torch.empty(x.size, dtype=torch.int16, device=DEV))
+        nm.nm_pwl_apply(xd, 1.0, dt, ti, inv, out_q=yq, out_f32=yf, dbg_seg=ys)
+        assert_exact(host(ys).view(np.uint16), s, f"pwl_apply seg {f}")
+        assert_exact(host(yq), q, f"pwl_apply int8 {f}")
+        assert_f32_close(host(yf), y, f"pwl_apply fp32 {f}")
+    # int32 input with a dequantisation scale
+    g = np.random.default_rng(ti)
+    a = g.integers(-40000, 40000, size=70001, dtype=np.int32)
+    alpha = float(np.float32((hi - lo) / 60000.0))
+    y, q, s = oracle.pwl_apply(a, ot[ti], alpha=alpha, out_inv_scale=9.0)
+    yq = torch.empty(a.size, dtype=torch.int8, device=DEV)
+    ys = torch.empty(a.size, dtype=torch.int16, device=DEV)
+    nm.nm_pwl_apply(dev(a), alpha, dt, ti, 9.0, out_q=yq, dbg_seg=ys)
+    assert_exact(host(ys).view(np.uint16), s, "pwl_apply i32 seg")
+    assert_exact(host(yq), q, "pwl_apply i32 int8")
+
+
+def test_pwl_apply_edge_sizes_and_misaligned(oracle):
+    ot, dt = both_tables(oracle, SPECS[:1])
+    x = W.sweep_values(-8.0, 8.0, 64, seed=9)
+    for n in (0, 1, 3, 4, 5, 63, 64, 65):
+        big = dev(np.concatenate([np.zeros(1, np.float32), x[:n]]))
+        src = big[1:]                          # 4-byte but not 16-byte aligned
+        yq = torch.full((n + 9,), 77, dtype=torch.int8, device=DEV)
+        yf = torch.full((n + 9,), -5.0, dtype=torch.float32, device=DEV)
+        nm.nm_pwl_apply(src, 1.0, dt, 0, 8.0, out_q=yq[1:], out_f32=yf[1:], n=n)
+        y, q, _ = oracle.pwl_apply(x[:n], ot[0], out_inv_scale=8.0)
+        assert_exact(host(yq)[1:n + 1], q, "misaligned int8")
+        assert_f32_close(host(yf)[1:n + 1], y, "misaligned fp32")
+        assert np.all(host(yq)[n + 1:] == 77) and host(yq)[0] == 77   # nothing outside [0, n)
+        assert np.all(host(yf)[n + 1:] == -5.0)
+
+
+def test_clamp_input_flag(oracle):
+    ot, dt = both_tables(oracle, [("exp", -16.0, 0.0, 64)], flags=1)
+    x = W.sweep_values(-16.0, 0.0, 5000, seed=2)
+    y, q, s = oracle.pwl_apply(x, ot[0], out_inv_scale=100.0)
+    yf = torch.empty(x.size, dtype=torch.float32, device=DEV)
+    ys = torch.empty(x.size, dtype=torch.int16, device=DEV)
+    nm.nm_pwl_apply(dev(x), 1.0, dt, 0, 100.0, out_f32=yf, dbg_seg=ys)
+    assert_exact(host(ys).view(np.uint16), s, "clamp seg")
+    assert_f32_close(host(yf), y, "clamp fp32")
+
+
+# ---- softmax-PWL ------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols", [(37, 1), (37, 5), (19, 64), (101, 128), (37, 200), (37, 512),
+                                       (9, 777), (5, 1024), (3, 4096), (0, 128)])
+@pytest.mark.parametrize("dtype", ["i32", "f32"])
+def test_softmax_pwl(oracle, rows, cols, dtype):
+    ot, dt = both_tables(oracle, [("exp", -16.0, 0.0, 128), ("recip", 1.0, float(max(64, cols)), 128)])
+    a = W.score_rows(rows, cols, seed=rows * 7 + cols)
+    alpha = 3e-4
+    x = a if dtype == "i32" else (a.astype(np.float32) * np.float32(0.37))
+    r = oracle.softmax_pwl(x, alpha, ot[0], ot[1], 127.0) if rows else None
+    xd = dev(x)
+    oq = torch.empty((rows, cols), dtype=torch.int8, device=DEV)
+    of = torch.empty((rows, cols), dtype=torch.float32, device=DEV)
+    se = torch.empty((rows, cols), dtype=torch.int16, device=DEV)
+    sr = torch.empty((max(rows, 1),), dtype=torch.int16, device=DEV)
+    nm.nm_softmax_pwl(xd, alpha, dt, 0, 1, 127.0, out_q=oq, out_f32=of, dbg_seg_exp=se,
+                      dbg_seg_recip=sr, rows=rows, cols=cols)
+    torch.cuda.synchronize()
+    if rows == 0:
+        return
+    assert_exact(host(se).view(np.uint16), r["seg_exp"], "softmax exp segments")
+    assert_exact(host(sr).view(np.uint16)[:rows], r["seg_recip"], "softmax recip segments")
+    assert_exact(host(oq), r["q"], "softmax int8")
+    assert_f32_close(host(of), r["p"], f"softmax fp32 {rows}x{cols} {dtype}")
+
+
+def test_softmax_pwl_headline_shape_int8_only(oracle):
+    """The launch configuration the benchmark times: 32*12*128 rows of 128, int8 output only."""
+    rows, cols = 32 * 12 * 128, 128
+    ot, dt = both_tables(oracle, [("exp", -16.0, 0.0, 128), ("recip", 1.0, 128.0, 128)])
+    g = np.random.default_rng(5)
+    a = np.rint(800 * g.standard_normal((rows, cols))).astype(np.int32)
+    alpha = 6.1e-5
+    r = oracle.softmax_pwl(a, alpha, ot[0], ot[1], 127.0)
+    oq = torch.empty((rows, cols), dtype=torch.int8, device=DEV)
+    nm.nm_softmax_pwl(dev(a), alpha, dt, 0, 1, 127.0, out_q=oq)
+    assert_exact(host(oq), r["q"], "softmax int8 headline shape")
+
+
+# ---- LayerNorm-PWL ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols", [(37, 1), (37, 4), (37, 96), (101, 128), (37, 768), (9, 1000),
+                                       (37, 1024), (3, 4096), (5, 3000), (0, 768)])
+def test_layernorm_pwl(oracle, rows, cols):
+    ot, dt = both_tables(oracle, [("rsqrt", 1e-3, 64.0, 128)])
+    x = W.float_rows(rows, cols, seed=rows + cols)
+    g = np.random.default_rng(cols)
+    gamma = (1 + 0.1 * g.standard_normal(cols)).astype(np.float32)
+    beta = (0.1 * g.standard_normal(cols)).astype(np.float32)
+    oq = torch.empty((rows, cols), dtype=torch.int8, device=DEV)
+    of = torch.empty((rows, cols), dtype=torch.float32, device=DEV)
+    sg = torch.empty((max(rows, 1),), dtype=torch.int16, device=DEV)
+    nm.nm_layernorm_pwl(dev(x), dev(gamma), dev(beta), 1e-5, dt, 0, 31.0, out_q=oq, out_f32=of,
+                        dbg_seg=sg, rows=rows, cols=cols)
+    torch.cuda.synchronize()
+    if rows == 0:
+        return
+    r = oracle.layernorm_pwl(x, gamma, beta, 1e-5, ot[0], 31.0)
+    assert_exact(host(sg).view(np.uint16)[:rows], r["seg"], "layernorm segments")
+    assert_exact(host(oq), r["q"], "layernorm int8")
+    assert_f32_close(host(of), r["y"], f"layernorm fp32 {rows}x{cols}")
+
+
+def test_layernorm_pwl_headline_shape(oracle):
+    rows, cols = 4096, 768
+    ot, dt = both_tables(oracle, [("rsqrt", 1e-3, 64.0, 128)])
+    x = W.float_rows(rows, cols, seed=11, std=1.1)
+    g = np.random.default_rng(3)
+    gamma = (1 + 0.02 * g.standard_normal(cols)).astype(np.float32)
+    beta = (0.02 * g.standard_normal(cols)).astype(np.float32)
+    oq = torch.empty((rows, cols), dtype=torch.int8, device=DEV)
+    nm.nm_layernorm_pwl(dev(x), dev(gamma), dev(beta), 1e-5, dt, 0, 30.0, out_q=oq)
+    r = oracle.layernorm_pwl(x, gamma, beta, 1e-5, ot[0], 30.0)
+    assert_exact(host(oq), r["q"], "layernorm int8 headline shape")
+
+
+# ---- GEMM + epilogue --------------------------------------------------------------------------
+
+GEMM_SHAPES = [(1, 1, 1), (5, 7, 3), (33, 65, 130), (64, 48, 768), (200, 136, 64), (300, 200, 200),
+               (256, 384, 128), (129, 257, 80), (128, 64, 16), (7, 300, 1041)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_accumulators_bit_exact(oracle, M, N, K):
+    d = W.gemm_inputs(M, N, K, seed=M * 3 + N * 5 + K)
+    r = oracle.gemm_pwl(d["A"], d["W"])
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), out_acc=acc)
+    assert_exact(host(acc), r["acc"], f"gemm acc {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_full_epilogue(oracle, M, N, K):
+    ot, dt = both_tables(oracle, [("gelu", -8.0, 8.0, 128)])
+    d = W.gemm_inputs(M, N, K, seed=M + N + K, full_range=False)
+    alpha = float(np.float32(6.0 / (20 * 20 * np.sqrt(K))))
+    kw = dict(bias=d["bias"], alpha=alpha, resid=d["resid"], resid_scale=0.01, table=ot[0],
+              out_inv_scale=25.0)
+    r = oracle.gemm_pwl(d["A"], d["W"], **kw)
+    oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+    of = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    seg = torch.empty((M, N), dtype=torch.int16, device=DEV)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, resid=dev(d["resid"]),
+                   resid_scale=0.01, tables=dt, table_idx=0, out_inv_scale=25.0, out_q=oq,
+                   out_f32=of, out_acc=acc, dbg_seg=seg)
+    assert_exact(host(acc), r["acc"], "gemm acc")
+    assert_exact(host(seg).view(np.uint16), r["seg"], "gemm GELU segments")
+    assert_exact(host(oq), r["q"], "gemm int8")
+    assert_f32_close(host(of), r["y"], f"gemm fp32 {M}x{N}x{K}")
+    assert len(np.unique(r["seg"])) > 3 or M * N < 50  # the inputs do exercise the table
+
+
+@pytest.mark.parametrize("M,N,K", [(33, 65, 130), (256, 384, 128)])
+def test_gemm_per_column_scales_no_table(oracle, M, N, K):
+    d = W.gemm_inputs(M, N, K, seed=7)
+    r = oracle.gemm_pwl(d["A"], d["W"], alpha_vec=d["alpha_vec"] * 1e-3,
+                        out_inv_scale_vec=d["out_inv_scale_vec"], bias=d["bias"])
+    oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+    of = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]),
+                   alpha_vec=dev((d["alpha_vec"] * 1e-3).astype(np.float32)),
+                   out_inv_scale_vec=dev(d["out_inv_scale_vec"]), out_q=oq, out_f32=of)
+    assert_exact(host(oq), r["q"], "gemm per-column int8")
+    assert_f32_close(host(of), r["y"], "gemm per-column fp32")
+
+
+def test_gemm_extreme_operands(oracle):
+    """All-(-127) x all-(+127) at the largest K of the workloads: |acc| = K * 127^2 > 2^24."""
+    M, N, K = 40, 72, 3072
+    A = np.full((M, K), -127, np.int8)
+    Wm = np.full((N, K), 127, np.int8)
+    r = oracle.gemm_pwl(A, Wm, alpha=1e-6)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    of = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    nm.nm_gemm_pwl(dev(A), dev(Wm), alpha=1e-6, out_acc=acc, out_f32=of)
+    assert_exact(host(acc), r["acc"], "extreme acc")
+    assert_f32_close(host(of), r["y"], "extreme fp32")
+
+
+def test_gemm_headline_ffn1_sampled(oracle):
+    """FFN1 of the headline configuration (4096 x 3072 x 768) with the GELU table, in the launch
+    configuration the benchmark times; 64 full output rows are checked against the oracle."""
+    M, N, K = 4096, 3072, 768
+    ot, dt = both_tables(oracle, [("gelu", -8.0, 8.0, 128)])
+    d = W.gemm_inputs(M, N, K, seed=1, full_range=False)
+    alpha = float(np.float32(1.5e-3))
+    oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=dt, table_idx=0,
+                   out_inv_scale=20.0, out_q=oq)
+    rows = np.random.default_rng(0).choice(M, 64, replace=False)
+    r = oracle.gemm_pwl(d["A"][rows], d["W"], bias=d["bias"], alpha=alpha, table=ot[0], out_inv_scale=20.0)
+    assert_exact(host(oq)[rows], r["q"], "FFN1 sampled rows")
+
+
+# ---- attention products -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,S,H,heads", [(1, 64, 128, 2), (3, 40, 96, 3), (2, 128, 768, 12), (1, 200, 64, 1),
+                                         (2, 33, 40, 5)])
+def test_attention_scores_and_context(oracle, B, S, H, heads):
+    g = np.random.default_rng(B + S + H)
+    d = H // heads
+    qkv = g.integers(-127, 128, size=(B * S, 3 * H), dtype=np.int8)
+    q4 = qkv[:, :H].reshape(B, S, heads, d).astype(np.int64)
+    k4 = qkv[:, H:2 * H].reshape(B, S, heads, d).astype(np.int64)
+    v4 = qkv[:, 2 * H:].reshape(B, S, heads, d).astype(np.int64)
+    want = np.einsum("bihc,bjhc->bhij", q4, k4)   # the oracle layer's scores equal this (CPU pin)
+    sc = torch.empty((B, heads, S, S), dtype=torch.int32, device=DEV)
+    nm.nm_attn_scores(dev(qkv), B, S, H, heads, sc)
+    assert_exact(host(sc).astype(np.int64), want, "scores")
+    p = g.integers(0, 128, size=(B, heads, S, S), dtype=np.int8)
+    cacc = np.einsum("bhij,bjhc->bihc", p.astype(np.int64), v4).reshape(B * S, H)
+    alpha, inv = float(np.float32(1.0 / (127 * S))), float(np.float32(3.0))
+    v = (cacc.astype(np.float32) * np.float32(alpha)).astype(np.float32)
+    want_ctx = np.array([oracle.requant(x, inv) for x in v.ravel()[:4096]])
+    ctx = torch.empty((B * S, H), dtype=torch.int8, device=DEV)
+    nm.nm_attn_context(dev(p), dev(qkv), B, S, H, heads, alpha, inv, ctx)
+    assert np.abs(cacc).max() < 2 ** 24
+    assert_exact(host(ctx).ravel()[:4096], want_ctx, "context (first 4096)")
+    full = np.clip(np.rint((v * np.float32(inv)).astype(np.float32)), -127, 127).astype(np.int8)
+    assert_exact(host(ctx), full, "context")
+
+
+# ---- encoder layer ----------------------------------------------------------------------------
+
+def run_layer(oracle, name, library_tables=False, seed=0):
+    cfg = W.config(name)
+    p = W.layer_params(name, seed)
+    specs = [W.table_ranges(cfg)[n] for n in ("gelu", "exp", "recip", "rsqrt")]
+    ot, dt = both_tables(oracle, specs)
+    if library_tables:
+        dt = nm.nm_build_tables(specs)
+    tb = dict(zip(("gelu", "exp", "recip", "rsqrt"), ot))
+    want = oracle.encoder_layer(p, tb, p["x"])
+    B, S, H, nh, F = (cfg[k] for k in ("B", "S", "H", "heads", "F"))
+    M = B * S
+    devw = {n: dev(p[n]) for n in nm.LAYER_PTRS}
+    desc = nm.make_layer_desc(p, devw, dt)
+    ws = torch.empty(nm.nm_encoder_layer_workspace(desc), dtype=torch.uint8, device=DEV)
+    taps = dict(qkv=torch.empty((M, 3 * H), dtype=torch.int8, device=DEV),
+                scores=torch.empty((B, nh, S, S), dtype=torch.int32, device=DEV),
+                p=torch.empty((B, nh, S, S), dtype=torch.int8, device=DEV),
+                ctx=torch.empty((M, H), dtype=torch.int8, device=DEV),
+                attn=torch.empty((M, H), dtype=torch.float32, device=DEV),
+                ln1=torch.empty((M, H), dtype=torch.int8, device=DEV),
+                ffn1=torch.empty((M, F), dtype=torch.int8, device=DEV),
+                ffn2=torch.empty((M, H), dtype=torch.float32, device=DEV))
+    yq = torch.empty((M, H), dtype=torch.int8, device=DEV)
+    yf = torch.empty((M, H), dtype=torch.float32, device=DEV)
+    nm.nm_encoder_layer(desc, dev(p["x"]), yq, yf, ws, taps=taps)
+    got = {k: host(v) for k, v in taps.items()}
+    got["y_q"], got["y_f32"] = host(yq), host(yf)
+    # a second run without taps (intermediates in the workspace) must give the same output
+    yq2 = torch.empty_like(yq)
+    nm.nm_encoder_layer(desc, dev(p["x"]), yq2, None, ws)
+    assert_exact(host(yq2), got["y_q"], "layer output with workspace intermediates")
+    return want, got
+
+
+@pytest.mark.parametrize("name", ["tiny", "ragged", "bert_base_layer"])
+def test_encoder_layer_all_stages(oracle, name):
+    want, got = run_layer(oracle, name)
+    for k in ("qkv", "scores", "p", "ctx", "ln1", "ffn1", "y_q"):
+        assert_exact(got[k], want[k], f"{name} layer {k}")
+    for k in ("attn", "ffn2", "y_f32"):
+        assert_f32_close(got[k], want[k], f"{name} layer {k}")
+
+
+def test_encoder_layer_with_library_built_tables(oracle):
+    """The product path builds its own tables (host code of the library).  They may differ from
+    the oracle's in the last bit, so int8 outputs are compared to within one code."""
+    want, got = run_layer(oracle, "tiny", library_tables=True)
+    diff = np.abs(got["y_q"].astype(int) - want["y_q"].astype(int))
+    assert diff.max() <= 1 and (diff > 0).mean() < 1e-3
+    assert np.allclose(got["y_f32"], want["y_f32"], rtol=1e-4, atol=1e-5)
+
+
+def test_workspace_errors():
+    cfg = W.config("tiny")
+    p = W.layer_params("tiny", 0)
+    specs = [W.table_ranges(cfg)[n] for n in ("gelu", "exp", "recip", "rsqrt")]
+    dt = nm.nm_build_tables(specs)
+    devw = {n: dev(p[n]) for n in nm.LAYER_PTRS}
+    desc = nm.make_layer_desc(p, devw, dt)
+    need = nm.nm_encoder_layer_workspace(desc)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    yq = torch.empty((64, 128), dtype=torch.int8, device=DEV)
+    with pytest.raises(nm.NmError) as ei:
+        nm.nm_encoder_layer(desc, dev(p["x"]), yq, None, ws, ws_bytes=need - 1)
+    assert ei.value.status == nm.NM_ERR_WORKSPACE
+    with pytest.raises(nm.NmError) as ei:
+        nm.nm_encoder_layer(desc, dev(p["x"]), yq, None, ws[1:], ws_bytes=need)
+    assert ei.value.status == nm.NM_ERR_WORKSPACE
+    d2, k, b, inv_w = nm.nm_tables_get(dt, 1)
+    assert d2.nseg == specs[1][3] and k.shape == (specs[1][3],) and nm.nm_tables_count(dt) == 4
