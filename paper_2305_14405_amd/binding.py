@@ -77,8 +77,13 @@ def load(preload_torch: bool = True) -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with "
                           "`python -m paper_2305_14405_amd.build` (there is no CPU fallback)")
-    if preload_torch:
+    # torch bundles its own HIP runtime; it must be in the process before this library is, so that
+    # both resolve to the same runtime (device pointers and streams are shared between them)
+    del preload_torch
+    try:
         import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(LIB_PATH)
     L.nm_last_error.restype = C.c_char_p
     L.nm_table_build_host.argtypes = [C.POINTER(TableDesc), C.c_void_p, C.c_void_p, C.c_void_p,

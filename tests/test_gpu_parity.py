@@ -39,8 +39,9 @@ def assert_f32_close(got, want, what):
     want = np.asarray(want)
     assert got.shape == want.shape
     tol = 1e-5 * np.abs(want) + 1e-30
-    bad = ~((np.abs(got.astype(np.float64) - want.astype(np.float64)) <= tol) |
-            (np.isnan(got) & np.isnan(want)))
+    with np.errstate(invalid="ignore"):
+        bad = ~((np.abs(got.astype(np.float64) - want.astype(np.float64)) <= tol) | (got == want) |
+                (np.isnan(got) & np.isnan(want)))
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} beyond 1e-5 relative"
     nbits = int((got.view(np.uint32) != want.view(np.uint32)).sum())
     print(f"[parity] {what}: fp32 within 1e-5 relative; {nbits} of {got.size} not bit-identical")
