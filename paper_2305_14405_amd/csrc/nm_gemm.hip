@@ -19,6 +19,8 @@
 // Both operands are K-contiguous, which is what the int8 MFMA wants: a lane feeds 16 consecutive
 // k of one row.  The same k of A and W always meet in the same (lane group, byte) slot, and int32
 // addition is exact, so results do not depend on tiling, on the k order or on any split of K.
+#include <cstdlib>
+
 #include "nm_device.h"
 
 namespace nm {
@@ -45,6 +47,8 @@ struct GemmParams {
     float inv3[3];
     long ldo;
     int vec_out;
+    int q16;       // int8 output rows may be written with 16-byte stores
+    int vec_cols;  // bias / per-column scale vectors may be read with 16-byte loads
     int8_t* out_q;
     float* out_f32;
     int32_t* out_acc;
@@ -54,6 +58,13 @@ struct GemmParams {
 
 // XOR swizzle of the 16-byte chunk index inside a 64-byte LDS row: rows that fall into the same
 // bank window get different chunk positions, for both a 128-byte and a 256-byte wide LDS port.
+// Debug switch: NM_GEMM_GENERIC=1 in the environment sends every shape to the generic kernel.
+static bool force_generic()
+{
+    static const bool v = [] { const char* e = getenv("NM_GEMM_GENERIC"); return e && e[0] == '1'; }();
+    return v;
+}
+
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 2) & 3); }
 
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * kBK + ((chunk ^ swz(row)) << 4); }
@@ -82,6 +93,122 @@ __device__ __forceinline__ v4i load_chunk(const int8_t* __restrict__ X, long ld,
     return v;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Epilogue shared by both kernels.  A lane holds, for one output row m, four consecutive columns
+// nb .. nb+3 (one group of four accumulator registers).
+// ---------------------------------------------------------------------------------------------
+// Epilogue specialisations: the generic one reads every option at run time; the others fix the
+// set of outputs and options the encoder layer uses, which removes dead code from the unrolled
+// epilogue (it is instantiated once per accumulator group).
+enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4 };
+
+struct Epi4 {
+    float y[4];
+    int q[4];
+    int s[4];
+};
+
+// Per-column parameters of four consecutive columns, loaded once and reused for every row.
+struct Col4 {
+    float scale[4], bias[4], inv[4];
+};
+
+__device__ __forceinline__ void load4(const float* __restrict__ v, int nb, int N, bool vec, float (&out)[4])
+{
+    if (vec && nb + 3 < N) {
+        const v4f t = *reinterpret_cast<const v4f*>(v + nb);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = t[e];
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (nb + e < N) out[e] = v[nb + e];
+    }
+}
+
+template <int kEpi>
+__device__ __forceinline__ void load_cols(const GemmParams& p, int nb, Col4& c)
+{
+    const float alpha = p.alpha, ois = p.out_inv_scale;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { c.scale[e] = alpha; c.bias[e] = 0.0f; c.inv[e] = ois; }
+    if (kEpi == EPI_ACC) return;
+    if (p.bias) load4(p.bias, nb, p.N, p.vec_cols, c.bias);
+    if (kEpi == EPI_GENERIC && p.alpha_vec) load4(p.alpha_vec, nb, p.N, p.vec_cols, c.scale);
+    if (kEpi == EPI_F32_RESID) return;
+    if (kEpi == EPI_GENERIC && p.out_inv_scale_vec) {
+        load4(p.out_inv_scale_vec, nb, p.N, p.vec_cols, c.inv);
+    } else if (p.split_cols > 0) {
+        const float i0 = p.inv3[0], i1 = p.inv3[1], i2 = p.inv3[2];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c.inv[e] = nb + e >= 2 * p.split_cols ? i2 : (nb + e >= p.split_cols ? i1 : i0);
+    }
+}
+
+template <int kEpi>
+__device__ __forceinline__ void epi_compute(const GemmParams& p, const float2* s_kb, long rowoff,
+                                            int nb, const int (&a4)[4], const Col4& c, bool vec, Epi4& o)
+{
+    const bool use_resid = kEpi == EPI_GENERIC ? p.resid != nullptr : kEpi == EPI_F32_RESID;
+    const bool use_table = kEpi == EPI_GENERIC ? p.has_table != 0 : kEpi == EPI_Q_TABLE;
+    const bool need_q = kEpi == EPI_GENERIC ? p.out_q != nullptr : (kEpi == EPI_Q || kEpi == EPI_Q_TABLE);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { o.y[e] = 0.0f; o.q[e] = 0; o.s[e] = 0; }
+    if (kEpi == EPI_ACC) return;
+    int r4[4] = {0, 0, 0, 0};
+    if (use_resid) {
+        if (vec) {
+            const unsigned w = *reinterpret_cast<const unsigned*>(p.resid + rowoff + nb);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r4[e] = (int)(int8_t)(w >> (8 * e));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (nb + e < p.N) r4[e] = (int)p.resid[rowoff + nb + e];
+        }
+    }
+    const float rs = p.resid_scale;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float v = __builtin_fmaf((float)a4[e], c.scale[e], c.bias[e]);
+        if (use_resid) v = __builtin_fmaf((float)r4[e], rs, v);
+        if (use_table) v = pwl_eval(v, p.table, s_kb, o.s[e]);
+        o.y[e] = v;
+        if (need_q) o.q[e] = requant(v, c.inv[e]);
+    }
+}
+
+template <int kEpi>
+__device__ __forceinline__ void epi_store(const GemmParams& p, long rowoff, int nb,
+                                          const int (&a4)[4], const Epi4& o, bool vec, bool skip_q)
+{
+    const bool st_q = (kEpi == EPI_GENERIC ? p.out_q != nullptr : (kEpi == EPI_Q || kEpi == EPI_Q_TABLE)) && !skip_q;
+    const bool st_f = kEpi == EPI_GENERIC ? p.out_f32 != nullptr : kEpi == EPI_F32_RESID;
+    const bool st_a = kEpi == EPI_GENERIC ? p.out_acc != nullptr : kEpi == EPI_ACC;
+    const bool st_s = kEpi == EPI_GENERIC && p.dbg_seg && p.has_table;
+    if (vec) {
+        if (st_q) *reinterpret_cast<unsigned*>(p.out_q + rowoff + nb) = pack4(o.q[0], o.q[1], o.q[2], o.q[3]);
+        if (st_f) *reinterpret_cast<v4f*>(p.out_f32 + rowoff + nb) = v4f{o.y[0], o.y[1], o.y[2], o.y[3]};
+        if (st_a) *reinterpret_cast<v4i*>(p.out_acc + rowoff + nb) = v4i{a4[0], a4[1], a4[2], a4[3]};
+        if (st_s)
+            *reinterpret_cast<uint2*>(p.dbg_seg + rowoff + nb) =
+                make_uint2((unsigned)o.s[0] | ((unsigned)o.s[1] << 16), (unsigned)o.s[2] | ((unsigned)o.s[3] << 16));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (nb + e < p.N) {
+                if (st_q) p.out_q[rowoff + nb + e] = (int8_t)o.q[e];
+                if (st_f) p.out_f32[rowoff + nb + e] = o.y[e];
+                if (st_a) p.out_acc[rowoff + nb + e] = a4[e];
+                if (st_s) p.dbg_seg[rowoff + nb + e] = (uint16_t)o.s[e];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic kernel: any shape and alignment, W as [N, K] or [K, N].  Operands go global -> registers
+// -> LDS (two stages); out-of-range rows and the k tail are zero-filled.
+// ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int WM, int WN, bool kAligned, bool kWKN>
 __global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
 {
@@ -190,60 +317,214 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
         __syncthreads();
     }
 
-    // ---- epilogue: lane owns row m; registers 4g .. 4g+3 are columns nb .. nb+3 ----------------
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wave_m + 32 * i + frag_row;
-        if (m >= p.M) continue;
-        const long rowoff = obase + (long)m * p.ldo;
+    for (int j = 0; j < TN; ++j) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+        for (int g = 0; g < 4; ++g) {
+            const int nb = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
+            if (nb >= p.N) continue;
+            const bool vec = p.vec_out && nb + 3 < p.N;
+            Col4 c;
+            load_cols<EPI_GENERIC>(p, nb, c);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int nb = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
-                if (nb >= p.N) continue;
-                const bool full = nb + 3 < p.N;
-                int a4[4], q4[4], s4[4];
-                float y4[4];
-                unsigned res_word = 0;
-                const bool vec = p.vec_out && full;
-                if (p.resid && vec) res_word = *reinterpret_cast<const unsigned*>(p.resid + rowoff + nb);
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + wave_m + 32 * i + frag_row;
+                if (m >= p.M) continue;
+                const long rowoff = obase + (long)m * p.ldo;
+                int a4[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int n = nb + e;
-                    a4[e] = acc[i][j][4 * g + e];
-                    y4[e] = 0.0f; q4[e] = 0; s4[e] = 0;
-                    if (n < p.N) {
-                        const float scale = p.alpha_vec ? p.alpha_vec[n] : p.alpha;
-                        float v = __builtin_fmaf((float)a4[e], scale, p.bias ? p.bias[n] : 0.0f);
-                        if (p.resid) {
-                            const int r = vec ? (int)(int8_t)(res_word >> (8 * e)) : (int)p.resid[rowoff + n];
-                            v = __builtin_fmaf((float)r, p.resid_scale, v);
-                        }
-                        if (p.has_table) v = pwl_eval(v, p.table, s_kb, s4[e]);
-                        y4[e] = v;
-                        float inv = p.out_inv_scale;
-                        if (p.out_inv_scale_vec) inv = p.out_inv_scale_vec[n];
-                        else if (p.split_cols > 0) inv = p.inv3[min(n / p.split_cols, 2)];
-                        q4[e] = requant(v, inv);
-                    }
-                }
-                if (vec) {
-                    if (p.out_q) *reinterpret_cast<unsigned*>(p.out_q + rowoff + nb) = pack4(q4[0], q4[1], q4[2], q4[3]);
-                    if (p.out_f32) *reinterpret_cast<v4f*>(p.out_f32 + rowoff + nb) = v4f{y4[0], y4[1], y4[2], y4[3]};
-                    if (p.out_acc) *reinterpret_cast<v4i*>(p.out_acc + rowoff + nb) = v4i{a4[0], a4[1], a4[2], a4[3]};
-                    if (p.dbg_seg && p.has_table)
-                        *reinterpret_cast<uint2*>(p.dbg_seg + rowoff + nb) =
-                            make_uint2((unsigned)s4[0] | ((unsigned)s4[1] << 16), (unsigned)s4[2] | ((unsigned)s4[3] << 16));
+                for (int e = 0; e < 4; ++e) a4[e] = acc[i][j][4 * g + e];
+                Epi4 o;
+                epi_compute<EPI_GENERIC>(p, s_kb, rowoff, nb, a4, c, vec, o);
+                epi_store<EPI_GENERIC>(p, rowoff, nb, a4, o, vec, false);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Streaming kernel for the shapes of the encoder layer: K a multiple of 64, 16-byte aligned rows,
+// W as [N, K].  Operands go global -> LDS directly (global_load_lds_dwordx4: a wavefront
+// instruction moves 64 x 16 bytes into 1 KB of consecutive LDS, no registers in between) through
+// a ring of kStages stages; a wavefront waits with an explicit vmcnt for the stage it is about to
+// use while the loads of the later stages stay in flight.  The LDS image of a stage is
+// (BM + BN) rows of 64 bytes: 16 consecutive rows per wavefront instruction, with the chunk
+// swizzle applied on the global side (lane p of an instruction fetches row p/4, logical chunk
+// (p%4) ^ swz(row)).  Rows past the matrix edge are clamped to the last row: they only feed
+// accumulators that are never stored.
+// Workgroups are numbered so that the eight XCDs (workgroup id mod 8) each own a compact block of
+// output tiles: the A rows and W rows a block needs fit that XCD's L2.
+// int8 output goes through a per-wavefront LDS patch so that rows leave as 16-byte stores.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(gptr)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int kStages, int kEpi>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(GemmParams p)
+{
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int ROWS = BM + BN;
+    constexpr int NBLK = ROWS / 16;              // 1 KB blocks (16 rows) per stage
+    constexpr int LB = (NBLK + NW - 1) / NW;     // blocks per wavefront (some have LB - 1)
+    constexpr int STAGE_BYTES = ROWS * kBK;
+    constexpr int SW = WN + 16;                  // row stride of the int8 output patch
+    static_assert(BM % 32 == 0 && BN % 32 == 0 && ROWS % 16 == 0, "tile shape");
+    static_assert(WM * SW * NW <= kStages * STAGE_BYTES, "output patch fits the operand ring");
+    static_assert(kStages == 3, "the vmcnt bookkeeping below is written for three stages");
+
+    extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+    float2* s_kb = reinterpret_cast<float2*>(smem + kStages * STAGE_BYTES);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = (wave / WAVES_N) * WM;
+    const int wave_n = (wave % WAVES_N) * WN;
+
+    // XCD-aware tile order: ids that share (id mod 8) are renumbered to be consecutive, then
+    // consecutive ids fill groups of 8 tile rows column by column
+    int id = blockIdx.x;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    if (ntiles % 8 == 0) id = (id % 8) * (ntiles / 8) + id / 8;
+    constexpr int GM = 8;
+    const int group = id / (GM * p.tiles_n);
+    const int first_m = group * GM;
+    const int gm = min(GM, p.tiles_m - first_m);
+    const int in_group = id - group * GM * p.tiles_n;
+    const int tile_m = first_m + in_group % gm;
+    const int tile_n = in_group / gm;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int outer = blockIdx.y / p.inner_count;
+    const int inner = blockIdx.y % p.inner_count;
+    const int8_t* __restrict__ A = p.A + outer * p.a_outer + inner * p.a_inner;
+    const int8_t* __restrict__ W = p.W + outer * p.w_outer + inner * p.w_inner;
+    const long obase = outer * p.o_outer + inner * p.o_inner;
+
+    if (p.has_table) stage_table(s_kb, p.table);
+
+    // per-lane source pointers of this wavefront's blocks (k = 0)
+    const int8_t* src[LB];
+    const bool has_last = wave + (LB - 1) * NW < NBLK;  // wave-uniform
+#pragma unroll
+    for (int b = 0; b < LB; ++b) {
+        int blk = wave + b * NW;
+        if (blk >= NBLK) blk = wave;  // unused slot
+        const int r = blk * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ swz(r);
+        if (r < BM) src[b] = A + (long)min(m0 + r, p.M - 1) * p.lda + 16 * chunk;
+        else src[b] = W + (long)min(n0 + r - BM, p.N - 1) * p.ldw + 16 * chunk;
+    }
+    const unsigned lds_base = (unsigned)(uintptr_t)smem;
+    auto issue = [&](int kt, int stage) {
+        const unsigned dst = lds_base + stage * STAGE_BYTES + wave * 1024;
+#pragma unroll
+        for (int b = 0; b < LB; ++b)
+            if (b < LB - 1 || has_last) dma16(src[b] + (long)kt * kBK, dst + b * NW * 1024);
+    };
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    const int nk = p.K / kBK;
+    issue(0, 0);
+    if (nk > 1) issue(1, 1);
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    int stage = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        // the loads of stage kt are older than those of kt + 1: let only the younger ones fly
+        if (kt + 1 < nk) {
+            if (has_last) wait_vmcnt<LB>(); else wait_vmcnt<LB - 1>();
+        } else {
+            wait_vmcnt<0>();
+        }
+        __syncthreads();  // stage kt has landed for every wavefront; stage kt - 1 is free again
+        int nxt = stage + 2;
+        if (nxt >= kStages) nxt -= kStages;
+        if (kt + 2 < nk) issue(kt + 2, nxt);
+        const int8_t* sA = smem + stage * STAGE_BYTES;
+        const int8_t* sW = sA + BM * kBK;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i fa[TM], fw[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const v4i*>(&sA[lds_off(wave_m + 32 * i + frag_row, 2 * ks + frag_half)]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fw[j] = *reinterpret_cast<const v4i*>(&sW[lds_off(wave_n + 32 * j + frag_row, 2 * ks + frag_half)]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+        stage = stage + 1 == kStages ? 0 : stage + 1;
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------------
+    const bool patch_q = (kEpi == EPI_GENERIC || kEpi == EPI_Q || kEpi == EPI_Q_TABLE) &&
+                         p.out_q != nullptr && p.q16;  // uniform: int8 rows leave through LDS
+    __syncthreads();                                   // every wavefront is done with the ring
+    int8_t* patch = smem + wave * (WM * SW);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nb = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
+            if (nb >= p.N) continue;
+            const bool vec = p.vec_out && nb + 3 < p.N;
+            Col4 c;
+            load_cols<kEpi>(p, nb, c);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + wave_m + 32 * i + frag_row;
+                if (m >= p.M) continue;
+                const long rowoff = obase + (long)m * p.ldo;
+                int a4[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a4[e] = acc[i][j][4 * g + e];
+                Epi4 o;
+                epi_compute<kEpi>(p, s_kb, rowoff, nb, a4, c, vec, o);
+                epi_store<kEpi>(p, rowoff, nb, a4, o, vec, patch_q);
+                if (patch_q)
+                    *reinterpret_cast<unsigned*>(patch + (32 * i + frag_row) * SW + 32 * j + 8 * g + 4 * frag_half) =
+                        pack4(o.q[0], o.q[1], o.q[2], o.q[3]);
+            }
+        }
+    }
+    if (patch_q) {
+        __syncthreads();
+        constexpr int CPR = WN / 16;  // 16-byte chunks per patch row
+        for (int c = lane; c < WM * CPR; c += 64) {
+            const int row = c / CPR, cc = c % CPR;
+            const int m = m0 + wave_m + row, n = n0 + wave_n + 16 * cc;
+            if (m < p.M && n < p.N) {
+                const v4i v = *reinterpret_cast<const v4i*>(patch + row * SW + 16 * cc);
+                int8_t* dst = p.out_q + obase + (long)m * p.ldo + n;
+                if (n + 15 < p.N) {
+                    *reinterpret_cast<v4i*>(dst) = v;
                 } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (nb + e < p.N) {
-                            if (p.out_q) p.out_q[rowoff + nb + e] = (int8_t)q4[e];
-                            if (p.out_f32) p.out_f32[rowoff + nb + e] = y4[e];
-                            if (p.out_acc) p.out_acc[rowoff + nb + e] = a4[e];
-                            if (p.dbg_seg && p.has_table) p.dbg_seg[rowoff + nb + e] = (uint16_t)s4[e];
-                        }
+                    for (int b = 0; b < 16 && n + b < p.N; ++b)
+                        dst[b] = (int8_t)((unsigned)v[b >> 2] >> (8 * (b & 3)));
                 }
             }
         }
@@ -257,6 +538,38 @@ static void launch_cfg(const GemmParams& p, bool al, bool wkn, dim3 grid, size_t
     else if (!al && !wkn) hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, false, false>), grid, dim3(kGemmThreads), shmem, s, p);
     else if (al && wkn) hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, true, true>), grid, dim3(kGemmThreads), shmem, s, p);
     else hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, false, true>), grid, dim3(kGemmThreads), shmem, s, p);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int kEpi>
+static int32_t launch_stream_epi(GemmParams& p, int batches, size_t table_bytes, hipStream_t s)
+{
+    constexpr int kStages = 3;
+    auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, kStages, kEpi>;
+    const size_t shmem = (size_t)kStages * (BM + BN) * kBK + table_bytes;
+    static bool configured = false;  // one attribute call per instantiation
+    if (!configured) {
+        int32_t rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
+                               "hipFuncSetAttribute(gemm_stream_kernel)");
+        if (rc) return rc;
+        configured = true;
+    }
+    p.tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.N + BN - 1) / BN;
+    hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, batches), dim3(64 * WAVES_M * WAVES_N), shmem, s, p);
+    return NM_OK;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+static int32_t launch_stream(GemmParams& p, int epi, int batches, size_t table_bytes, hipStream_t s)
+{
+    switch (epi) {
+    case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_Q>(p, batches, table_bytes, s);
+    case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_Q_TABLE>(p, batches, table_bytes, s);
+    case EPI_F32_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_F32_RESID>(p, batches, table_bytes, s);
+    case EPI_ACC: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_ACC>(p, batches, table_bytes, s);
+    default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_GENERIC>(p, batches, table_bytes, s);
+    }
 }
 
 int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
@@ -285,17 +598,34 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
                 (!g.out_q || aligned(g.out_q, 4)) && (!g.out_f32 || aligned(g.out_f32, 16)) &&
                 (!g.out_acc || aligned(g.out_acc, 16)) && (!g.dbg_seg || aligned(g.dbg_seg, 8)) &&
                 (!g.resid || aligned(g.resid, 4));
+    p.q16 = g.out_q && aligned(g.out_q, 16) && g.ldo % 16 == 0 && g.o_outer % 16 == 0 && g.o_inner % 16 == 0;
 
-    const size_t shmem = g.has_table ? sizeof(float2) * (size_t)g.table.nseg : 0;
+    const size_t table_bytes = g.has_table ? sizeof(float2) * (size_t)g.table.nseg : 0;
     const int batches = g.outer_count * g.inner_count;
     if (batches > 65535) return fail(NM_ERR_UNSUPPORTED, "gemm: more than 65535 batched problems");
-    if (g.N <= 64) {
+    int32_t rc = NM_OK;
+    p.vec_cols = (!g.bias || aligned(g.bias, 16)) && (!g.alpha_vec || aligned(g.alpha_vec, 16)) &&
+                 (!g.out_inv_scale_vec || aligned(g.out_inv_scale_vec, 16));
+    int epi = EPI_GENERIC;
+    if (!g.alpha_vec && !g.out_inv_scale_vec && !g.dbg_seg) {
+        const bool only_q = g.out_q && !g.out_f32 && !g.out_acc;
+        if (only_q && !g.resid) epi = g.has_table ? EPI_Q_TABLE : EPI_Q;
+        else if (g.out_f32 && !g.out_q && !g.out_acc && g.resid && !g.has_table) epi = EPI_F32_RESID;
+        else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
+    }
+    const bool stream_ok = al && !g.w_is_kn && g.K % kBK == 0 && !force_generic();
+    if (stream_ok && g.N >= 1536 && g.M >= 256) {
+        rc = launch_stream<256, 192, 4, 2>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && g.N > 64) {
+        rc = launch_stream<128, 128, 2, 2>(p, epi, batches, table_bytes, stream);
+    } else if (g.N <= 64) {
         p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 63) / 64;
-        launch_cfg<128, 64, 32, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), shmem, stream);
+        launch_cfg<128, 64, 32, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), table_bytes, stream);
     } else {
         p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 127) / 128;
-        launch_cfg<128, 128, 64, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), shmem, stream);
+        launch_cfg<128, 128, 64, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), table_bytes, stream);
     }
+    if (rc) return rc;
     return check_hip(hipGetLastError(), "gemm launch");
 }
 
