@@ -64,6 +64,12 @@ static bool force_generic()
     static const bool v = [] { const char* e = getenv("NM_GEMM_GENERIC"); return e && e[0] == '1'; }();
     return v;
 }
+// Debug switch: NM_GEMM_TILE=mid keeps every shape on the 128x128 streaming tile.
+static bool force_mid_tile()
+{
+    static const bool v = [] { const char* e = getenv("NM_GEMM_TILE"); return e && e[0] == 'm'; }();
+    return v;
+}
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 2) & 3); }
 
@@ -145,9 +151,23 @@ __device__ __forceinline__ void load_cols(const GemmParams& p, int nb, Col4& c)
     }
 }
 
+// Residual codes of four consecutive columns of one row.
+__device__ __forceinline__ void load_resid4(const GemmParams& p, long rowoff, int nb, bool vec, int (&r4)[4])
+{
+    if (vec) {
+        const unsigned w = *reinterpret_cast<const unsigned*>(p.resid + rowoff + nb);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r4[e] = (int)(int8_t)(w >> (8 * e));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r4[e] = nb + e < p.N ? (int)p.resid[rowoff + nb + e] : 0;
+    }
+}
+
+// The arithmetic of the epilogue for four columns of one row (no global memory access).
 template <int kEpi>
-__device__ __forceinline__ void epi_compute(const GemmParams& p, const float2* s_kb, long rowoff,
-                                            int nb, const int (&a4)[4], const Col4& c, bool vec, Epi4& o)
+__device__ __forceinline__ void epi_math(const GemmParams& p, const float2* s_kb, const int (&a4)[4],
+                                         const Col4& c, const int (&r4)[4], Epi4& o)
 {
     const bool use_resid = kEpi == EPI_GENERIC ? p.resid != nullptr : kEpi == EPI_F32_RESID;
     const bool use_table = kEpi == EPI_GENERIC ? p.has_table != 0 : kEpi == EPI_Q_TABLE;
@@ -155,18 +175,6 @@ __device__ __forceinline__ void epi_compute(const GemmParams& p, const float2* s
 #pragma unroll
     for (int e = 0; e < 4; ++e) { o.y[e] = 0.0f; o.q[e] = 0; o.s[e] = 0; }
     if (kEpi == EPI_ACC) return;
-    int r4[4] = {0, 0, 0, 0};
-    if (use_resid) {
-        if (vec) {
-            const unsigned w = *reinterpret_cast<const unsigned*>(p.resid + rowoff + nb);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) r4[e] = (int)(int8_t)(w >> (8 * e));
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (nb + e < p.N) r4[e] = (int)p.resid[rowoff + nb + e];
-        }
-    }
     const float rs = p.resid_scale;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -334,8 +342,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
                 int a4[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) a4[e] = acc[i][j][4 * g + e];
+                int r4[4] = {0, 0, 0, 0};
+                if (p.resid) load_resid4(p, rowoff, nb, vec, r4);
                 Epi4 o;
-                epi_compute<EPI_GENERIC>(p, s_kb, rowoff, nb, a4, c, vec, o);
+                epi_math<EPI_GENERIC>(p, s_kb, a4, c, r4, o);
                 epi_store<EPI_GENERIC>(p, rowoff, nb, a4, o, vec, false);
             }
         }
@@ -386,7 +396,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
     static_assert(kStages == 3, "the vmcnt bookkeeping below is written for three stages");
 
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
-    float2* s_kb = reinterpret_cast<float2*>(smem + kStages * STAGE_BYTES);
+    float* s_cols = reinterpret_cast<float*>(smem + kStages * STAGE_BYTES);  // scale | bias | inv, BN each
+    float2* s_kb = reinterpret_cast<float2*>(s_cols + 3 * BN);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -414,6 +425,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
     const long obase = outer * p.o_outer + inner * p.o_inner;
 
     if (p.has_table) stage_table(s_kb, p.table);
+    // per-column epilogue parameters of this tile go to LDS now (their latency hides behind the
+    // main loop) so that the epilogue itself issues no global loads for them
+    if (kEpi != EPI_ACC) {
+        for (int t = tid; t < BN; t += 64 * NW) {
+            const int n = n0 + t;
+            float sc = p.alpha, bi = 0.0f, iv = p.out_inv_scale;
+            if (n < p.N) {
+                if (p.bias) bi = p.bias[n];
+                if (kEpi == EPI_GENERIC && p.alpha_vec) sc = p.alpha_vec[n];
+                if (kEpi == EPI_GENERIC && p.out_inv_scale_vec) iv = p.out_inv_scale_vec[n];
+                else if (p.split_cols > 0) iv = n >= 2 * p.split_cols ? p.inv3[2] : (n >= p.split_cols ? p.inv3[1] : p.inv3[0]);
+            }
+            s_cols[t] = sc;
+            s_cols[BN + t] = bi;
+            s_cols[2 * BN + t] = iv;
+        }
+    }
 
     // per-lane source pointers of this wavefront's blocks (k = 0)
     const int8_t* src[LB];
@@ -485,15 +513,38 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
                          p.out_q != nullptr && p.q16;  // uniform: int8 rows leave through LDS
     __syncthreads();                                   // every wavefront is done with the ring
     int8_t* patch = smem + wave * (WM * SW);
+    // the specialised residual epilogue fetches all of the lane's residual words up front
+    unsigned resw[TM][TN][4];
+    if (kEpi == EPI_F32_RESID) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int m = m0 + wave_m + 32 * i + frag_row;
+                    const int nb = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
+                    resw[i][j][g] = 0;
+                    if (m < p.M && nb + 3 < p.N)
+                        resw[i][j][g] = *reinterpret_cast<const unsigned*>(p.resid + obase + (long)m * p.ldo + nb);
+                }
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int nb = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
+            const int cl = wave_n + 32 * j + 8 * g + 4 * frag_half;  // column inside the tile
+            const int nb = n0 + cl;
             if (nb >= p.N) continue;
             const bool vec = p.vec_out && nb + 3 < p.N;
             Col4 c;
-            load_cols<kEpi>(p, nb, c);
+            {
+                const v4f sc = *reinterpret_cast<const v4f*>(s_cols + cl);
+                const v4f bi = *reinterpret_cast<const v4f*>(s_cols + BN + cl);
+                const v4f iv = *reinterpret_cast<const v4f*>(s_cols + 2 * BN + cl);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { c.scale[e] = sc[e]; c.bias[e] = bi[e]; c.inv[e] = iv[e]; }
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int m = m0 + wave_m + 32 * i + frag_row;
@@ -502,8 +553,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
                 int a4[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) a4[e] = acc[i][j][4 * g + e];
+                int r4[4] = {0, 0, 0, 0};
+                if (kEpi == EPI_F32_RESID) {
+                    if (nb + 3 < p.N) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) r4[e] = (int)(int8_t)(resw[i][j][g] >> (8 * e));
+                    } else {
+                        load_resid4(p, rowoff, nb, false, r4);
+                    }
+                } else if (kEpi == EPI_GENERIC && p.resid) {
+                    load_resid4(p, rowoff, nb, vec, r4);
+                }
                 Epi4 o;
-                epi_compute<kEpi>(p, s_kb, rowoff, nb, a4, c, vec, o);
+                epi_math<kEpi>(p, s_kb, a4, c, r4, o);
                 epi_store<kEpi>(p, rowoff, nb, a4, o, vec, patch_q);
                 if (patch_q)
                     *reinterpret_cast<unsigned*>(patch + (32 * i + frag_row) * SW + 32 * j + 8 * g + 4 * frag_half) =
@@ -545,7 +607,7 @@ static int32_t launch_stream_epi(GemmParams& p, int batches, size_t table_bytes,
 {
     constexpr int kStages = 3;
     auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, kStages, kEpi>;
-    const size_t shmem = (size_t)kStages * (BM + BN) * kBK + table_bytes;
+    const size_t shmem = (size_t)kStages * (BM + BN) * kBK + 3 * BN * sizeof(float) + table_bytes;
     static bool configured = false;  // one attribute call per instantiation
     if (!configured) {
         int32_t rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -610,11 +672,11 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     if (!g.alpha_vec && !g.out_inv_scale_vec && !g.dbg_seg) {
         const bool only_q = g.out_q && !g.out_f32 && !g.out_acc;
         if (only_q && !g.resid) epi = g.has_table ? EPI_Q_TABLE : EPI_Q;
-        else if (g.out_f32 && !g.out_q && !g.out_acc && g.resid && !g.has_table) epi = EPI_F32_RESID;
+        else if (g.out_f32 && !g.out_q && !g.out_acc && g.resid && !g.has_table && p.vec_out) epi = EPI_F32_RESID;
         else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
     }
     const bool stream_ok = al && !g.w_is_kn && g.K % kBK == 0 && !force_generic();
-    if (stream_ok && g.N >= 1536 && g.M >= 256) {
+    if (stream_ok && g.N >= 1536 && g.M >= 256 && !force_mid_tile()) {
         rc = launch_stream<256, 192, 4, 2>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && g.N > 64) {
         rc = launch_stream<128, 128, 2, 2>(p, epi, batches, table_bytes, stream);
