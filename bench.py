@@ -69,7 +69,10 @@ def main():
                 ffn2=torch.empty((M, H), dtype=torch.float32, device=dev))
 
     def step():
-        nm.nm_encoder_layer(desc, x, yq, None, ws, taps=taps)
+        # the hot path proper: intermediates live in the workspace, nothing optional is written
+        nm.nm_encoder_layer(desc, x, yq, None, ws)
+
+    nm.nm_encoder_layer(desc, x, yq, None, ws, taps=taps)  # fills the buffers the per-kernel timings read
 
     for _ in range(args.warmup):
         step()
@@ -100,14 +103,12 @@ def main():
         ("qkv_gemm", "mfma", 2.0 * M * 3 * H * H,
          lambda: nm.nm_gemm_pwl(x, devw["Wqkv"], bias=devw["bqkv"], alpha=p["alpha_qkv"],
                                 out_inv_scale_vec=osv, out_q=taps["qkv"])),
-        ("attn_scores", "hbm", float(M * 2 * H + B * nh * S * S * 4),
-         lambda: nm.nm_attn_scores(taps["qkv"], B, S, H, nh, taps["scores"])),
+        ("attention_fused", "hbm", float(M * 3 * H + M * H),
+         lambda: nm.nm_attention_pwl(taps["qkv"], B, S, H, nh, p["alpha_scores"], tables, 1, 2,
+                                     p["inv_s_p"], p["alpha_ctx"], p["inv_s_ctx"], taps["ctx"])),
         ("softmax_pwl", "hbm", float(B * nh * S * S * 5),
          lambda: nm.nm_softmax_pwl(taps["scores"].view(-1, S), p["alpha_scores"], tables, 1, 2,
                                    p["inv_s_p"], out_q=taps["p"].view(-1, S))),
-        ("attn_context", "hbm", float(B * nh * S * S + M * H + M * H),
-         lambda: nm.nm_attn_context(taps["p"], taps["qkv"], B, S, H, nh, p["alpha_ctx"],
-                                    p["inv_s_ctx"], taps["ctx"])),
         ("out_proj_gemm", "mfma", 2.0 * M * H * H,
          lambda: nm.nm_gemm_pwl(taps["ctx"], devw["Wo"], bias=devw["bo"], alpha=p["alpha_o"],
                                 resid=x, resid_scale=p["resid1_scale"], out_f32=taps["attn"])),
@@ -139,12 +140,13 @@ def main():
     gemm_ops = sum(2.0 * M * n * k for n, k in ((3 * H, H), (H, H), (F, H), (H, F)))
     gemm_ms = sum(k["ms"] for k in kernels if k["bound"] == "mfma")
     row_bytes = float(B * nh * S * S * 5 + 2 * M * H * 5)
-    row_ms = sum(k["ms"] for k in kernels if k["kernel"] in ("softmax_pwl", "layernorm_pwl")) + \
-        next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl")
+    ln_ms = next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl")
+    row_ms = next(k["ms"] for k in kernels if k["kernel"] == "softmax_pwl") + 2 * ln_ms
     summary = dict(int8_mfma_util_pct=round(100 * gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
                    nonlinear_hbm_gbs=round(row_bytes / (row_ms * 1e-3) / 1e9, 1),
-                   sum_kernel_ms=round(sum(k["ms"] for k in kernels) +
-                                       next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl"), 4))
+                   sum_kernel_ms=round(sum(k["ms"] for k in kernels if k["kernel"] != "softmax_pwl") + ln_ms, 4),
+                   note="softmax_pwl is the stand-alone row kernel (timed on its own; the layer uses the "
+                        "fused attention kernel at this shape); layernorm_pwl runs twice per layer")
 
     # ---- CPU oracle on the host cores: the same workload, bounded sample ----------------------
     cpu_baseline = None

@@ -105,8 +105,8 @@ int32_t nm_table_build_host(const nm_table_desc* desc, float* k, float* b, float
 /*
  * Build n tables on the host (as nm_table_build_host) and upload them as one device blob on
  * `stream`.  descs: host array of n descriptors, 1 <= n <= NM_MAX_TABLES.  *out receives a new
- * object owned by the caller (nm_tables_destroy).  The upload is complete when work queued on
- * `stream` after this call runs; other streams must synchronise with it themselves.
+ * object owned by the caller (nm_tables_destroy).  This is an offline call: it waits for the
+ * upload on `stream` before it returns, so the tables may be used from any stream afterwards.
  */
 int32_t nm_build_tables(const nm_table_desc* descs, int32_t n, void* stream, nm_tables** out);
 
@@ -224,6 +224,19 @@ int32_t nm_attn_scores(const int8_t* qkv, int32_t B, int32_t S, int32_t H, int32
 int32_t nm_attn_context(const int8_t* p, const int8_t* qkv, int32_t B, int32_t S, int32_t H,
                         int32_t heads, float alpha, float out_inv_scale, int8_t* ctx,
                         void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * nm_attention_pwl: the three attention steps in one kernel (scores, softmax-PWL, context), with
+ * results bit-identical to nm_attn_scores -> nm_softmax_pwl -> nm_attn_context; the int32 scores
+ * and the int8 probabilities stay in registers.  scores_out / p_out (device, [B,heads,S,S]) may be
+ * NULL; when given they receive the intermediate tensors.
+ * Limits: head size H / heads == 64, S <= 256, qkv 16-byte aligned, H % 16 == 0; other shapes
+ * return NM_ERR_UNSUPPORTED and the caller uses the three separate calls.
+ * --------------------------------------------------------------------------------------------- */
+int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int32_t H, int32_t heads,
+                         float alpha_scores, const nm_tables* tables, int32_t exp_idx,
+                         int32_t recip_idx, float inv_s_p, float alpha_ctx, float inv_s_ctx,
+                         int8_t* ctx, int32_t* scores_out, int8_t* p_out, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * nm_encoder_layer: one post-LayerNorm (BERT ordering) encoder layer, no mask, no dropout:

@@ -22,7 +22,7 @@ NM_DT_I32, NM_DT_F32 = 0, 1
 EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_tables",
            "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_destroy",
            "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_pwl_apply", "nm_attn_scores",
-           "nm_attn_context", "nm_encoder_layer_workspace", "nm_encoder_layer")
+           "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer")
 
 
 class NmError(RuntimeError):
@@ -110,6 +110,9 @@ def load(preload_torch: bool = True) -> C.CDLL:
                                  C.c_void_p, C.c_void_p]
     L.nm_attn_context.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_int32, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
+    L.nm_attention_pwl.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                   C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_float,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.nm_encoder_layer_workspace.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_size_t)]
     L.nm_encoder_layer.argtypes = [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.POINTER(LayerTaps), C.c_void_p]
@@ -275,6 +278,13 @@ def nm_attn_scores(qkv, B, S, H, heads, scores, stream=None):
 def nm_attn_context(p, qkv, B, S, H, heads, alpha, out_inv_scale, ctx, stream=None):
     _check(load().nm_attn_context(_ptr(p), _ptr(qkv), B, S, H, heads, alpha, out_inv_scale,
                                   _ptr(ctx), _stream(stream)))
+
+
+def nm_attention_pwl(qkv, B, S, H, heads, alpha_scores, tables: Tables, exp_idx, recip_idx, inv_s_p,
+                     alpha_ctx, inv_s_ctx, ctx, scores_out=None, p_out=None, stream=None):
+    _check(load().nm_attention_pwl(_ptr(qkv), B, S, H, heads, alpha_scores, tables.handle, exp_idx,
+                                   recip_idx, inv_s_p, alpha_ctx, inv_s_ctx, _ptr(ctx),
+                                   _ptr(scores_out), _ptr(p_out), _stream(stream)))
 
 
 def make_layer_desc(params: dict, dev: dict, tables: Tables, idx=(0, 1, 2, 3)) -> LayerDesc:

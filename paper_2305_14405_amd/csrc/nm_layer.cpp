@@ -2,9 +2,18 @@
 // launches on one stream (paper Section 3: linear operators as matrix products, nonlinear
 // operators as PWL tables).  Host code only: it validates, carves the workspace and queues the
 // nine steps; nothing is allocated and the host never waits for the GPU.
+#include <cstdlib>
+
 #include "nm_internal.h"
 
 namespace nm {
+
+// Debug switch: NM_ATTN_UNFUSED=1 keeps attention on the three separate kernels.
+static bool unfused_attention()
+{
+    static const bool v = [] { const char* e = getenv("NM_ATTN_UNFUSED"); return e && e[0] == '1'; }();
+    return v;
+}
 
 static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -107,14 +116,22 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
         g.ldo = 3L * H; g.out_q = qkv;
         if ((rc = launch_gemm(g, stream))) return rc;
     }
-    // 2: scores = Q K^T per (batch, head)
-    if ((rc = nm_attn_scores(qkv, B, S, H, nh, scores, stream))) return rc;
-    // 3: softmax-PWL over every score row
-    if ((rc = launch_softmax(scores, NM_DT_I32, d->alpha_scores, (int64_t)B * nh * S, S, t_exp, t_recip,
-                             d->inv_s_p, pm, nullptr, nullptr, nullptr, stream)))
-        return rc;
-    // 4: context = P V per (batch, head)
-    if ((rc = nm_attn_context(pm, qkv, B, S, H, nh, d->alpha_ctx, d->inv_s_ctx, ctx, stream))) return rc;
+    // 2-4: attention.  One fused kernel when the shape allows it (the scores and probabilities then
+    // stay in registers; the taps, if given, still receive them), else three kernels.
+    const bool fused = H / nh == 64 && S <= 256 && H % 16 == 0 && aligned(qkv, 16) && aligned(ctx, 4) &&
+                       (!(taps && taps->scores) || aligned(taps->scores, 16)) && !unfused_attention();
+    if (fused) {
+        if ((rc = nm_attention_pwl(qkv, B, S, H, nh, d->alpha_scores, d->tables, d->exp_idx, d->recip_idx,
+                                   d->inv_s_p, d->alpha_ctx, d->inv_s_ctx, ctx, taps ? taps->scores : nullptr,
+                                   taps ? taps->p : nullptr, stream)))
+            return rc;
+    } else {
+        if ((rc = nm_attn_scores(qkv, B, S, H, nh, scores, stream))) return rc;
+        if ((rc = launch_softmax(scores, NM_DT_I32, d->alpha_scores, (int64_t)B * nh * S, S, t_exp, t_recip,
+                                 d->inv_s_p, pm, nullptr, nullptr, nullptr, stream)))
+            return rc;
+        if ((rc = nm_attn_context(pm, qkv, B, S, H, nh, d->alpha_ctx, d->inv_s_ctx, ctx, stream))) return rc;
+    }
     // 5: output projection + bias + residual(x) -> fp32
     {
         GemmArgs g;

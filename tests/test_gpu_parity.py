@@ -300,6 +300,50 @@ def test_attention_scores_and_context(oracle, B, S, H, heads):
     assert_exact(host(ctx), full, "context")
 
 
+@pytest.mark.parametrize("B,S,heads", [(1, 64, 2), (2, 128, 12), (1, 200, 1), (2, 33, 1), (1, 256, 2), (3, 7, 2),
+                                        (1, 100, 3)])
+def test_fused_attention_matches_oracle_stages(oracle, B, S, heads):
+    """nm_attention_pwl against scores (int64 einsum), the oracle's softmax-PWL and the oracle's
+    requantisation of P V: scores, probabilities and context all bit-exact."""
+    H = 64 * heads
+    ot, dt = both_tables(oracle, [("exp", -16.0, 0.0, 128), ("recip", 1.0, float(max(64, S)), 128)])
+    g = np.random.default_rng(B * 1000 + S)
+    qkv = np.clip(np.rint(18 * g.standard_normal((B * S, 3 * H))), -127, 127).astype(np.int8)
+    q4 = qkv[:, :H].reshape(B, S, heads, 64).astype(np.int64)
+    k4 = qkv[:, H:2 * H].reshape(B, S, heads, 64).astype(np.int64)
+    v4 = qkv[:, 2 * H:].reshape(B, S, heads, 64).astype(np.int64)
+    scores = np.einsum("bihc,bjhc->bhij", q4, k4)
+    alpha_s, inv_p = float(np.float32(1.2e-3)), float(np.float32(127.0))
+    sm = oracle.softmax_pwl(scores.reshape(-1, S).astype(np.int32), alpha_s, ot[0], ot[1], inv_p)
+    P = sm["q"].reshape(B, heads, S, S)
+    cacc = np.einsum("bhij,bjhc->bihc", P.astype(np.int64), v4).reshape(B * S, H)
+    assert np.abs(cacc).max() < 2 ** 24
+    alpha_c, inv_c = float(np.float32(2.0e-3)), float(np.float32(1.7))
+    cv = (cacc.astype(np.float32) * np.float32(alpha_c)).astype(np.float32)
+    want_ctx = np.clip(np.rint((cv * np.float32(inv_c)).astype(np.float32)), -127, 127).astype(np.int8)
+    ctx = torch.empty((B * S, H), dtype=torch.int8, device=DEV)
+    sc = torch.empty((B, heads, S, S), dtype=torch.int32, device=DEV)
+    pp = torch.empty((B, heads, S, S), dtype=torch.int8, device=DEV)
+    nm.nm_attention_pwl(dev(qkv), B, S, H, heads, alpha_s, dt, 0, 1, inv_p, alpha_c, inv_c, ctx, sc, pp)
+    assert_exact(host(sc).astype(np.int64), scores, "fused scores")
+    assert_exact(host(pp), P, "fused probabilities")
+    assert_exact(host(ctx), want_ctx, "fused context")
+    assert len(np.unique(sm["seg_exp"])) > 4  # the exp table is exercised
+    # without the optional outputs the context is the same
+    ctx2 = torch.empty_like(ctx)
+    nm.nm_attention_pwl(dev(qkv), B, S, H, heads, alpha_s, dt, 0, 1, inv_p, alpha_c, inv_c, ctx2)
+    assert_exact(host(ctx2), want_ctx, "fused context, no taps")
+
+
+def test_fused_attention_unsupported_shapes():
+    dt = nm.nm_build_tables([("exp", -16.0, 0.0, 64), ("recip", 1.0, 64.0, 64)])
+    x = torch.zeros((8 * 96 * 3,), dtype=torch.int8, device=DEV)
+    for (B, S, H, heads) in [(1, 8, 96, 3), (1, 300, 64, 1)]:
+        with pytest.raises(nm.NmError) as ei:
+            nm.nm_attention_pwl(x, B, S, H, heads, 1.0, dt, 0, 1, 1.0, 1.0, 1.0, x)
+        assert ei.value.status == nm.NM_ERR_UNSUPPORTED
+
+
 # ---- encoder layer ----------------------------------------------------------------------------
 
 def run_layer(oracle, name, library_tables=False, seed=0):
