@@ -380,20 +380,37 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int kStages, int kEpi>
+// LDS offset of (row, 16-byte chunk) for rows of BK bytes.  BK = 64: four chunks, the swizzle of
+// the generic kernel.  BK = 128: eight chunks, 16 consecutive rows spread over all chunk positions
+// of two adjacent rows' worth of banks.
+template <int BK>
+__device__ __forceinline__ int swz_bk(int row)
+{
+    return BK == 64 ? swz(row) : ((row >> 1) & 7);
+}
+template <int BK>
+__device__ __forceinline__ int lds_off_bk(int row, int chunk)
+{
+    return row * BK + ((chunk ^ swz_bk<BK>(row)) << 4);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int kStages, int kEpi>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(GemmParams p)
 {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int ROWS = BM + BN;
-    constexpr int NBLK = ROWS / 16;              // 1 KB blocks (16 rows) per stage
+    constexpr int CPR = BK / 16;                 // 16-byte chunks per LDS row
+    constexpr int RPI = 64 / CPR;                // rows moved by one wavefront instruction (1 KB)
+    constexpr int NBLK = ROWS / RPI;             // 1 KB blocks per stage
     constexpr int LB = (NBLK + NW - 1) / NW;     // blocks per wavefront (some have LB - 1)
-    constexpr int STAGE_BYTES = ROWS * kBK;
+    constexpr int STAGE_BYTES = ROWS * BK;
     constexpr int SW = WN + 16;                  // row stride of the int8 output patch
-    static_assert(BM % 32 == 0 && BN % 32 == 0 && ROWS % 16 == 0, "tile shape");
+    static_assert(BK == 64 || BK == 128, "k-slice of 64 or 128 bytes");
+    static_assert(BM % 32 == 0 && BN % 32 == 0 && ROWS % RPI == 0, "tile shape");
     static_assert(WM * SW * NW <= kStages * STAGE_BYTES, "output patch fits the operand ring");
-    static_assert(kStages == 3, "the vmcnt bookkeeping below is written for three stages");
+    static_assert(kStages >= 2 && kStages <= 4, "ring depth");
 
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     float* s_cols = reinterpret_cast<float*>(smem + kStages * STAGE_BYTES);  // scale | bias | inv, BN each
@@ -450,17 +467,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
     for (int b = 0; b < LB; ++b) {
         int blk = wave + b * NW;
         if (blk >= NBLK) blk = wave;  // unused slot
-        const int r = blk * 16 + (lane >> 2);
-        const int chunk = (lane & 3) ^ swz(r);
+        const int r = blk * RPI + lane / CPR;
+        const int chunk = (lane % CPR) ^ swz_bk<BK>(r);
         if (r < BM) src[b] = A + (long)min(m0 + r, p.M - 1) * p.lda + 16 * chunk;
         else src[b] = W + (long)min(n0 + r - BM, p.N - 1) * p.ldw + 16 * chunk;
     }
     const unsigned lds_base = (unsigned)(uintptr_t)smem;
-    auto issue = [&](int kt, int stage) {
+    // Issue the loads of k-slice kt into ring slot `stage`; with KS > 1 only the blocks b with
+    // b % KS == part, so that the issue slots can be spread between the MFMAs of the main loop
+    // (a wavefront issues in order: a burst of LB loads would stall its MFMA stream).
+    auto issue = [&](int kt, int stage, int part, int parts) {
         const unsigned dst = lds_base + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
         for (int b = 0; b < LB; ++b)
-            if (b < LB - 1 || has_last) dma16(src[b] + (long)kt * kBK, dst + b * NW * 1024);
+            if (b % parts == part && (b < LB - 1 || has_last)) dma16(src[b] + (long)kt * BK, dst + b * NW * 1024);
     };
 
     v16i acc[TM][TN];
@@ -471,39 +491,42 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    const int nk = p.K / kBK;
-    issue(0, 0);
-    if (nk > 1) issue(1, 1);
+    const int nk = p.K / BK;
+#pragma unroll
+    for (int st = 0; st < kStages - 1; ++st)
+        if (st < nk) issue(st, st, 0, 1);
 
     const int frag_row = lane & 31, frag_half = lane >> 5;
     int stage = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        // the loads of stage kt are older than those of kt + 1: let only the younger ones fly
-        if (kt + 1 < nk) {
-            if (has_last) wait_vmcnt<LB>(); else wait_vmcnt<LB - 1>();
-        } else {
-            wait_vmcnt<0>();
-        }
+        // The loads of stage kt are older than those of the stages issued after it: wait until only
+        // the younger ones are in flight.  `young` = number of younger stages already issued.
+        const int young = min(kStages - 2, nk - 1 - kt);
+        if (young <= 0) wait_vmcnt<0>();
+        else if (young == 1) { if (has_last) wait_vmcnt<LB>(); else wait_vmcnt<LB - 1>(); }
+        else { if (has_last) wait_vmcnt<2 * LB>(); else wait_vmcnt<2 * (LB - 1)>(); }
         __syncthreads();  // stage kt has landed for every wavefront; stage kt - 1 is free again
-        int nxt = stage + 2;
+        int nxt = stage + kStages - 1;
         if (nxt >= kStages) nxt -= kStages;
-        if (kt + 2 < nk) issue(kt + 2, nxt);
+        const bool more = kt + kStages - 1 < nk;
         const int8_t* sA = smem + stage * STAGE_BYTES;
-        const int8_t* sW = sA + BM * kBK;
+        const int8_t* sW = sA + BM * BK;
+        constexpr int KS = BK / 32;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             v4i fa[TM], fw[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const v4i*>(&sA[lds_off(wave_m + 32 * i + frag_row, 2 * ks + frag_half)]);
+                fa[i] = *reinterpret_cast<const v4i*>(&sA[lds_off_bk<BK>(wave_m + 32 * i + frag_row, 2 * ks + frag_half)]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fw[j] = *reinterpret_cast<const v4i*>(&sW[lds_off(wave_n + 32 * j + frag_row, 2 * ks + frag_half)]);
+                fw[j] = *reinterpret_cast<const v4i*>(&sW[lds_off_bk<BK>(wave_n + 32 * j + frag_row, 2 * ks + frag_half)]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fa[i], acc[i][j], 0, 0, 0);
+            if (more) issue(kt + kStages - 1, nxt, ks, KS);  // in the shadow of the MFMAs just issued
         }
         stage = stage + 1 == kStages ? 0 : stage + 1;
     }
@@ -602,12 +625,11 @@ static void launch_cfg(const GemmParams& p, bool al, bool wkn, dim3 grid, size_t
     else hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, false, true>), grid, dim3(kGemmThreads), shmem, s, p);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int kEpi>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int kStages, int kEpi>
 static int32_t launch_stream_epi(GemmParams& p, int batches, size_t table_bytes, hipStream_t s)
 {
-    constexpr int kStages = 3;
-    auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, kStages, kEpi>;
-    const size_t shmem = (size_t)kStages * (BM + BN) * kBK + 3 * BN * sizeof(float) + table_bytes;
+    auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, BK, kStages, kEpi>;
+    const size_t shmem = (size_t)kStages * (BM + BN) * BK + 3 * BN * sizeof(float) + table_bytes;
     static bool configured = false;  // one attribute call per instantiation
     if (!configured) {
         int32_t rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -622,15 +644,15 @@ static int32_t launch_stream_epi(GemmParams& p, int batches, size_t table_bytes,
     return NM_OK;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int kStages>
 static int32_t launch_stream(GemmParams& p, int epi, int batches, size_t table_bytes, hipStream_t s)
 {
     switch (epi) {
-    case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_Q>(p, batches, table_bytes, s);
-    case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_Q_TABLE>(p, batches, table_bytes, s);
-    case EPI_F32_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_F32_RESID>(p, batches, table_bytes, s);
-    case EPI_ACC: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_ACC>(p, batches, table_bytes, s);
-    default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, EPI_GENERIC>(p, batches, table_bytes, s);
+    case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_Q>(p, batches, table_bytes, s);
+    case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_Q_TABLE>(p, batches, table_bytes, s);
+    case EPI_F32_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_F32_RESID>(p, batches, table_bytes, s);
+    case EPI_ACC: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_ACC>(p, batches, table_bytes, s);
+    default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_GENERIC>(p, batches, table_bytes, s);
     }
 }
 
@@ -675,11 +697,17 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         else if (g.out_f32 && !g.out_q && !g.out_acc && g.resid && !g.has_table && p.vec_out) epi = EPI_F32_RESID;
         else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
     }
-    const bool stream_ok = al && !g.w_is_kn && g.K % kBK == 0 && !force_generic();
-    if (stream_ok && g.N >= 1536 && g.M >= 256 && !force_mid_tile()) {
-        rc = launch_stream<256, 192, 4, 2>(p, epi, batches, table_bytes, stream);
+    const bool stream_ok = al && !g.w_is_kn && g.K % 64 == 0 && !force_generic();
+    const bool k128 = g.K % 128 == 0;  // 128-byte k-slices (whole L2 lines) fetch ~1.5x faster than 64-byte ones
+    if (stream_ok && k128 && g.N >= 1536 && g.M >= 256 && !force_mid_tile()) {
+        rc = launch_stream<256, 192, 4, 2, 128, 2>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && k128 && g.N > 64 && g.K >= 512 && table_bytes <= 16384) {
+        // four 32 KB stages: a single workgroup per CU needs ~100 KB in flight to cover the latency
+        rc = launch_stream<128, 128, 2, 2, 128, 4>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && k128 && g.N > 64) {
+        rc = launch_stream<128, 128, 2, 2, 128, 3>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && g.N > 64) {
-        rc = launch_stream<128, 128, 2, 2>(p, epi, batches, table_bytes, stream);
+        rc = launch_stream<128, 128, 2, 2, 64, 3>(p, epi, batches, table_bytes, stream);
     } else if (g.N <= 64) {
         p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 63) / 64;
         launch_cfg<128, 64, 32, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), table_bytes, stream);
