@@ -394,12 +394,21 @@ __device__ __forceinline__ int lds_off_bk(int row, int chunk)
     return row * BK + ((chunk ^ swz_bk<BK>(row)) << 4);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int kStages, int kEpi>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(GemmParams p)
+// KSPLIT = 2 doubles the wavefronts of a workgroup without shrinking the wavefront tile: two
+// wavefronts share each WM x WN sub-tile and take alternate 32-byte k-steps of every k-slice (so
+// the LDS read traffic and the operand traffic stay those of the KSPLIT = 1 kernel, while each
+// SIMD has two wavefronts whose LDS waits and MFMAs overlap).  After the main loop the two swap
+// halves of their int32 partial accumulators through LDS (integer addition is exact in any
+// order) and each finishes half of the sub-tile's rows, which also halves the epilogue per
+// wavefront.  Used where the grid has fewer workgroups than CUs times two (N = 768 GEMMs).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages, int kEpi>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_kernel(GemmParams p)
 {
-    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int NWT = WAVES_M * WAVES_N;       // wavefront tiles per workgroup
+    constexpr int NW = NWT * KSPLIT;             // wavefronts per workgroup
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int TMF = TM / KSPLIT;             // 32-row blocks a wavefront finishes
     constexpr int ROWS = BM + BN;
     constexpr int CPR = BK / 16;                 // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPR;                // rows moved by one wavefront instruction (1 KB)
@@ -407,9 +416,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
     constexpr int LB = (NBLK + NW - 1) / NW;     // blocks per wavefront (some have LB - 1)
     constexpr int STAGE_BYTES = ROWS * BK;
     constexpr int SW = WN + 16;                  // row stride of the int8 output patch
+    constexpr int KS = BK / 32;                  // MFMA k-steps per k-slice
+    constexpr int KSW = KS / KSPLIT;             // ... per wavefront
     static_assert(BK == 64 || BK == 128, "k-slice of 64 or 128 bytes");
+    static_assert(KSPLIT == 1 || KSPLIT == 2, "one or two wavefronts per sub-tile");
+    static_assert(TM % KSPLIT == 0 && KS % KSPLIT == 0, "halves split evenly");
     static_assert(BM % 32 == 0 && BN % 32 == 0 && ROWS % RPI == 0, "tile shape");
-    static_assert(WM * SW * NW <= kStages * STAGE_BYTES, "output patch fits the operand ring");
+    static_assert(WM * SW * NWT <= kStages * STAGE_BYTES, "output patch fits the operand ring");
+    static_assert(KSPLIT == 1 || NW * TMF * TN * 4096 <= kStages * STAGE_BYTES, "exchange fits the ring");
     static_assert(kStages >= 2 && kStages <= 4, "ring depth");
 
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
@@ -419,8 +433,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_m = (wave / WAVES_N) * WM;
-    const int wave_n = (wave % WAVES_N) * WN;
+    const int wave_t = wave % NWT;               // which sub-tile
+    const int kg = wave / NWT;                   // which half of the k-steps (0 when KSPLIT == 1)
+    const int wave_m = (wave_t / WAVES_N) * WM;
+    const int wave_n = (wave_t % WAVES_N) * WN;
 
     // XCD-aware tile order: ids that share (id mod 8) are renumbered to be consecutive, then
     // consecutive ids fill groups of 8 tile rows column by column
@@ -473,8 +489,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
         else src[b] = W + (long)min(n0 + r - BM, p.N - 1) * p.ldw + 16 * chunk;
     }
     const unsigned lds_base = (unsigned)(uintptr_t)smem;
-    // Issue the loads of k-slice kt into ring slot `stage`; with KS > 1 only the blocks b with
-    // b % KS == part, so that the issue slots can be spread between the MFMAs of the main loop
+    // Issue the loads of k-slice kt into ring slot `stage`; with parts > 1 only the blocks b with
+    // b % parts == part, so that the issue slots can be spread between the MFMAs of the main loop
     // (a wavefront issues in order: a burst of LB loads would stall its MFMA stream).
     auto issue = [&](int kt, int stage, int part, int parts) {
         const unsigned dst = lds_base + stage * STAGE_BYTES + wave * 1024;
@@ -497,6 +513,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
         if (st < nk) issue(st, st, 0, 1);
 
     const int frag_row = lane & 31, frag_half = lane >> 5;
+    // LDS offsets of this lane's fragments inside a stage, per k-step this wavefront owns
+    int offA[KSW][TM], offW[KSW][TN];
+#pragma unroll
+    for (int kk = 0; kk < KSW; ++kk) {
+        const int ks = KSPLIT == 1 ? kk : kg + KSPLIT * kk;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) offA[kk][i] = lds_off_bk<BK>(wave_m + 32 * i + frag_row, 2 * ks + frag_half);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) offW[kk][j] = BM * BK + lds_off_bk<BK>(wave_n + 32 * j + frag_row, 2 * ks + frag_half);
+    }
     int stage = 0;
     for (int kt = 0; kt < nk; ++kt) {
         // The loads of stage kt are older than those of the stages issued after it: wait until only
@@ -509,43 +535,68 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
         int nxt = stage + kStages - 1;
         if (nxt >= kStages) nxt -= kStages;
         const bool more = kt + kStages - 1 < nk;
-        const int8_t* sA = smem + stage * STAGE_BYTES;
-        const int8_t* sW = sA + BM * BK;
-        constexpr int KS = BK / 32;
+        const int8_t* st = smem + stage * STAGE_BYTES;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        for (int kk = 0; kk < KSW; ++kk) {
             v4i fa[TM], fw[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const v4i*>(&sA[lds_off_bk<BK>(wave_m + 32 * i + frag_row, 2 * ks + frag_half)]);
+            for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const v4i*>(st + offA[kk][i]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fw[j] = *reinterpret_cast<const v4i*>(&sW[lds_off_bk<BK>(wave_n + 32 * j + frag_row, 2 * ks + frag_half)]);
+            for (int j = 0; j < TN; ++j) fw[j] = *reinterpret_cast<const v4i*>(st + offW[kk][j]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fa[i], acc[i][j], 0, 0, 0);
-            if (more) issue(kt + kStages - 1, nxt, ks, KS);  // in the shadow of the MFMAs just issued
+            if (more) issue(kt + kStages - 1, nxt, kk, KSW);  // in the shadow of the MFMAs just issued
         }
         stage = stage + 1 == kStages ? 0 : stage + 1;
     }
 
+    // ---- combine the two k-halves (KSPLIT == 2): swap accumulator halves through LDS ----------
+    v16i fin[TMF][TN];
+    __syncthreads();  // every wavefront is done with the ring
+    if (KSPLIT == 2) {
+        int* xch = reinterpret_cast<int*>(smem);
+        const int mine = (wave_t * 2 + kg) * (TMF * TN * 1024), other = (wave_t * 2 + (1 - kg)) * (TMF * TN * 1024);
+#pragma unroll
+        for (int i = 0; i < TMF; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)  // give away the row blocks the partner finishes
+                    xch[mine + ((i * TN + j) * 16 + v) * 64 + lane] = kg == 0 ? acc[TMF + i][j][v] : acc[i][j][v];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TMF; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    fin[i][j][v] = (kg == 0 ? acc[i][j][v] : acc[TMF + i][j][v]) + xch[other + ((i * TN + j) * 16 + v) * 64 + lane];
+        __syncthreads();  // the exchange area is about to become the output patch
+    } else {
+#pragma unroll
+        for (int i = 0; i < TMF; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fin[i][j] = acc[i][j];
+    }
+    const int row_blk0 = kg * TMF;  // first 32-row block of the sub-tile this wavefront finishes
+
     // ---- epilogue ------------------------------------------------------------------------------
     const bool patch_q = (kEpi == EPI_GENERIC || kEpi == EPI_Q || kEpi == EPI_Q_TABLE) &&
                          p.out_q != nullptr && p.q16;  // uniform: int8 rows leave through LDS
-    __syncthreads();                                   // every wavefront is done with the ring
-    int8_t* patch = smem + wave * (WM * SW);
+    int8_t* patch = smem + wave_t * (WM * SW);
     // the specialised residual epilogue fetches all of the lane's residual words up front
-    unsigned resw[TM][TN][4];
+    unsigned resw[TMF][TN][4];
     if (kEpi == EPI_F32_RESID) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TMF; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int m = m0 + wave_m + 32 * i + frag_row;
+                    const int m = m0 + wave_m + 32 * (row_blk0 + i) + frag_row;
                     const int nb = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
                     resw[i][j][g] = 0;
                     if (m < p.M && nb + 3 < p.N)
@@ -569,13 +620,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
                 for (int e = 0; e < 4; ++e) { c.scale[e] = sc[e]; c.bias[e] = bi[e]; c.inv[e] = iv[e]; }
             }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = m0 + wave_m + 32 * i + frag_row;
+            for (int i = 0; i < TMF; ++i) {
+                const int prow = 32 * (row_blk0 + i) + frag_row;  // row inside the sub-tile
+                const int m = m0 + wave_m + prow;
                 if (m >= p.M) continue;
                 const long rowoff = obase + (long)m * p.ldo;
                 int a4[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) a4[e] = acc[i][j][4 * g + e];
+                for (int e = 0; e < 4; ++e) a4[e] = fin[i][j][4 * g + e];
                 int r4[4] = {0, 0, 0, 0};
                 if (kEpi == EPI_F32_RESID) {
                     if (nb + 3 < p.N) {
@@ -591,16 +643,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_stream_kernel(Gem
                 epi_math<kEpi>(p, s_kb, a4, c, r4, o);
                 epi_store<kEpi>(p, rowoff, nb, a4, o, vec, patch_q);
                 if (patch_q)
-                    *reinterpret_cast<unsigned*>(patch + (32 * i + frag_row) * SW + 32 * j + 8 * g + 4 * frag_half) =
+                    *reinterpret_cast<unsigned*>(patch + prow * SW + 32 * j + 8 * g + 4 * frag_half) =
                         pack4(o.q[0], o.q[1], o.q[2], o.q[3]);
             }
         }
     }
     if (patch_q) {
         __syncthreads();
-        constexpr int CPR = WN / 16;  // 16-byte chunks per patch row
-        for (int c = lane; c < WM * CPR; c += 64) {
-            const int row = c / CPR, cc = c % CPR;
+        constexpr int PCPR = WN / 16;          // 16-byte chunks per patch row
+        constexpr int PROWS = WM / KSPLIT;     // patch rows this wavefront writes out
+        for (int c = lane; c < PROWS * PCPR; c += 64) {
+            const int row = kg * PROWS + c / PCPR, cc = c % PCPR;
             const int m = m0 + wave_m + row, n = n0 + wave_n + 16 * cc;
             if (m < p.M && n < p.N) {
                 const v4i v = *reinterpret_cast<const v4i*>(patch + row * SW + 16 * cc);
@@ -625,10 +678,10 @@ static void launch_cfg(const GemmParams& p, bool al, bool wkn, dim3 grid, size_t
     else hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, false, true>), grid, dim3(kGemmThreads), shmem, s, p);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int kStages, int kEpi>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages, int kEpi>
 static int32_t launch_stream_epi(GemmParams& p, int batches, size_t table_bytes, hipStream_t s)
 {
-    auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, BK, kStages, kEpi>;
+    auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, kEpi>;
     const size_t shmem = (size_t)kStages * (BM + BN) * BK + 3 * BN * sizeof(float) + table_bytes;
     static bool configured = false;  // one attribute call per instantiation
     if (!configured) {
@@ -640,19 +693,19 @@ static int32_t launch_stream_epi(GemmParams& p, int batches, size_t table_bytes,
     }
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, batches), dim3(64 * WAVES_M * WAVES_N), shmem, s, p);
+    hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, batches), dim3(64 * WAVES_M * WAVES_N * KSPLIT), shmem, s, p);
     return NM_OK;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int kStages>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages>
 static int32_t launch_stream(GemmParams& p, int epi, int batches, size_t table_bytes, hipStream_t s)
 {
     switch (epi) {
-    case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_Q>(p, batches, table_bytes, s);
-    case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_Q_TABLE>(p, batches, table_bytes, s);
-    case EPI_F32_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_F32_RESID>(p, batches, table_bytes, s);
-    case EPI_ACC: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_ACC>(p, batches, table_bytes, s);
-    default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, BK, kStages, EPI_GENERIC>(p, batches, table_bytes, s);
+    case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q>(p, batches, table_bytes, s);
+    case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q_TABLE>(p, batches, table_bytes, s);
+    case EPI_F32_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_F32_RESID>(p, batches, table_bytes, s);
+    case EPI_ACC: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_ACC>(p, batches, table_bytes, s);
+    default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_GENERIC>(p, batches, table_bytes, s);
     }
 }
 
@@ -700,14 +753,12 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     const bool stream_ok = al && !g.w_is_kn && g.K % 64 == 0 && !force_generic();
     const bool k128 = g.K % 128 == 0;  // 128-byte k-slices (whole L2 lines) fetch ~1.5x faster than 64-byte ones
     if (stream_ok && k128 && g.N >= 1536 && g.M >= 256 && !force_mid_tile()) {
-        rc = launch_stream<256, 192, 4, 2, 128, 2>(p, epi, batches, table_bytes, stream);
-    } else if (stream_ok && k128 && g.N > 64 && g.K >= 512 && table_bytes <= 16384) {
-        // four 32 KB stages: a single workgroup per CU needs ~100 KB in flight to cover the latency
-        rc = launch_stream<128, 128, 2, 2, 128, 4>(p, epi, batches, table_bytes, stream);
-    } else if (stream_ok && k128 && g.N > 64) {
-        rc = launch_stream<128, 128, 2, 2, 128, 3>(p, epi, batches, table_bytes, stream);
+        rc = launch_stream<256, 192, 4, 2, 1, 128, 2>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && k128 && g.N > 64 && table_bytes <= 32768) {
+        // few workgroups per CU: two wavefronts per sub-tile (k-steps split) keep every SIMD busy
+        rc = launch_stream<128, 128, 2, 2, 2, 128, 3>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && g.N > 64) {
-        rc = launch_stream<128, 128, 2, 2, 64, 3>(p, epi, batches, table_bytes, stream);
+        rc = launch_stream<128, 128, 2, 2, 1, 64, 3>(p, epi, batches, table_bytes, stream);
     } else if (g.N <= 64) {
         p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 63) / 64;
         launch_cfg<128, 64, 32, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), table_bytes, stream);
