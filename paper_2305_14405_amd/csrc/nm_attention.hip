@@ -39,7 +39,8 @@ constexpr int kHeadDim = 64;
 __device__ __forceinline__ int attn_swz(int row) { return ((row >> 1) & 3) ^ ((row >> 2) & 3); }
 __device__ __forceinline__ int attn_koff(int row, int chunk) { return row * 64 + ((chunk ^ attn_swz(row)) << 4); }
 
-template <int NB>
+// kFull: S == 32 * NB, so no key or query is masked (removes every per-key predicate).
+template <int NB, bool kFull>
 __global__ __launch_bounds__(kAttnThreads) void attention_pwl_kernel(AttnParams p)
 {
     constexpr int SK = NB * 32;   // padded key count
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(kAttnThreads) void attention_pwl_kernel(AttnParams 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, h = lane >> 5;
     const int b = blockIdx.y / p.heads, head = blockIdx.y % p.heads;
-    const int S = p.S, H = p.H;
+    const int S = kFull ? 32 * NB : p.S, H = p.H;
     const long ld = 3L * H;
     const int8_t* __restrict__ base = p.qkv + (long)b * S * ld + head * kHeadDim;
 
@@ -117,12 +118,12 @@ __global__ __launch_bounds__(kAttnThreads) void attention_pwl_kernel(AttnParams 
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int key = 32 * blk + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (key < S) mi = max(mi, acc[blk][v]);
+            if (kFull || key < S) mi = max(mi, acc[blk][v]);
         }
     mi = max(mi, __shfl_xor(mi, 32, 64));
 
+    // exp values replace the scores in place (same registers, float bits)
     float part[NB][4];
-    float ev[NB][16];
 #pragma unroll
     for (int blk = 0; blk < NB; ++blk)
 #pragma unroll
@@ -132,13 +133,13 @@ __global__ __launch_bounds__(kAttnThreads) void attention_pwl_kernel(AttnParams 
             for (int e = 0; e < 4; ++e) {
                 const int key = 32 * blk + 8 * g + 4 * h + e;
                 float x = 0.0f;
-                if (key < S) {
+                if (kFull || key < S) {
                     const float t = (float)(acc[blk][4 * g + e] - mi) * p.alpha_scores;
                     int seg;
                     x = pwl_eval(t, p.t_exp, s_kb, seg);
                     s = s + x;
                 }
-                ev[blk][4 * g + e] = x;
+                acc[blk][4 * g + e] = __float_as_int(x);
             }
             part[blk][g] = s;
         }
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(kAttnThreads) void attention_pwl_kernel(AttnParams 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int key = 32 * blk + 8 * g + 4 * h + e;
-                q[e] = key < S ? requant(ev[blk][4 * g + e] * r, p.inv_s_p) : 0;
+                q[e] = (kFull || key < S) ? requant(__int_as_float(acc[blk][4 * g + e]) * r, p.inv_s_p) : 0;
             }
             pk[blk][g] = pack4(q[0], q[1], q[2], q[3]);
         }
@@ -241,9 +242,15 @@ extern "C" int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int
     const dim3 grid((S + 127) / 128, B * heads);
     const size_t shmem = sizeof(float2) * (size_t)p.t_exp.nseg;
     hipStream_t st = (hipStream_t)stream;
-    if (S <= 32) hipLaunchKernelGGL(attention_pwl_kernel<1>, grid, dim3(kAttnThreads), shmem, st, p);
-    else if (S <= 64) hipLaunchKernelGGL(attention_pwl_kernel<2>, grid, dim3(kAttnThreads), shmem, st, p);
-    else if (S <= 128) hipLaunchKernelGGL(attention_pwl_kernel<4>, grid, dim3(kAttnThreads), shmem, st, p);
-    else hipLaunchKernelGGL(attention_pwl_kernel<8>, grid, dim3(kAttnThreads), shmem, st, p);
+#define NM_ATTN_LAUNCH(NBV)                                                                         \
+    do {                                                                                            \
+        if (S == 32 * NBV) hipLaunchKernelGGL((attention_pwl_kernel<NBV, true>), grid, dim3(kAttnThreads), shmem, st, p); \
+        else hipLaunchKernelGGL((attention_pwl_kernel<NBV, false>), grid, dim3(kAttnThreads), shmem, st, p);              \
+    } while (0)
+    if (S <= 32) NM_ATTN_LAUNCH(1);
+    else if (S <= 64) NM_ATTN_LAUNCH(2);
+    else if (S <= 128) NM_ATTN_LAUNCH(4);
+    else NM_ATTN_LAUNCH(8);
+#undef NM_ATTN_LAUNCH
     return check_hip(hipGetLastError(), "nm_attention_pwl launch");
 }
