@@ -13,19 +13,24 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 // Segment of x (paper Section 3.2: uniform segments, inputs outside the range use the edge
-// segments): one subtract, one multiply, clamp in float, floor.
+// segments): one subtract, one multiply, clamp in float, floor.  After the clamp u >= 0, so the
+// float -> int conversion (which truncates) IS the floor.
 __device__ __forceinline__ int seg_index(float x, float lo, float inv_w, int nseg)
 {
     float u = x - lo;
     u = u * inv_w;
     u = __builtin_fminf(__builtin_fmaxf(u, 0.0f), (float)(nseg - 1));
-    return (int)__builtin_floorf(u);
+    return (int)u;
 }
 
 // y = k[s]*x + b[s] (one fma).  kb may point to LDS or to global memory.
 __device__ __forceinline__ float pwl_eval(float x, const DevTable& t, const float2* kb, int& seg)
 {
-    if (t.clamp_input) x = __builtin_fminf(__builtin_fmaxf(x, t.lo), t.hi);
+    // one median-of-three plus a select (a branch here would split the caller's unrolled loops
+    // into small blocks and serialise their LDS gathers); NaN: med3 returns the smallest non-NaN
+    // operand, lo, as fmin(fmax(NaN, lo), hi) does
+    const float xc = __builtin_amdgcn_fmed3f(x, t.lo, t.hi);
+    x = t.clamp_input ? xc : x;
     seg = seg_index(x, t.lo, t.inv_w, t.nseg);
     float2 e = kb[seg];
     return __builtin_fmaf(e.x, x, e.y);

@@ -107,7 +107,8 @@ def test_pwl_apply_edge_sizes_and_misaligned(oracle):
 
 def test_clamp_input_flag(oracle):
     ot, dt = both_tables(oracle, [("exp", -16.0, 0.0, 64)], flags=1)
-    x = W.sweep_values(-16.0, 0.0, 5000, seed=2)
+    x = np.concatenate([W.sweep_values(-16.0, 0.0, 5000, seed=2),
+                        np.array([np.nan, np.inf, -np.inf, -16.0, 0.0], np.float32)])
     y, q, s = oracle.pwl_apply(x, ot[0], out_inv_scale=100.0)
     yf = torch.empty(x.size, dtype=torch.float32, device=DEV)
     ys = torch.empty(x.size, dtype=torch.int16, device=DEV)
