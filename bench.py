@@ -22,6 +22,29 @@ sys.path.insert(0, ROOT)
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, published: 5.0 POP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published: 8 TB/s
 
+# HBM-side traffic per launch at the bert_base_layer shapes, from two rocprofv3 --pmc runs of this
+# script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch).  A plain 64 MiB device copy in the same
+# runs read FETCH_SIZE = 32781 and WRITE_SIZE = 65536, so FETCH_SIZE is scaled by 65536 / 32781 and
+# WRITE_SIZE by 1.  Counters cannot be read from inside this process: these are recorded values,
+# refreshed when a kernel's memory behaviour changes.
+PMC_FETCH_SCALE = 65536.0 / 32781.0
+PMC_KIB = {  # kernel -> (FETCH_SIZE, WRITE_SIZE) as the counters read
+    "qkv_gemm": (8041.9, 9216.0),
+    "attention_fused": (9324.8, 5120.6),
+    "out_proj_gemm": (12178.7, 12288.6),   # counter average over out_proj and ffn2 (same kernel)
+    "ffn2_gemm": (12178.7, 12288.6),
+    "ffn1_gelu_gemm": (8678.6, 12288.0),
+    "layernorm_pwl": (6196.6, 3072.0),
+    "softmax_pwl": (12319.4, 6144.0),
+}
+
+
+def pmc_traffic_bytes(kernel):
+    if kernel not in PMC_KIB:
+        return None
+    f, w = PMC_KIB[kernel]
+    return int(round((f * PMC_FETCH_SCALE + w) * 1024))
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -31,6 +54,9 @@ def main():
     ap.add_argument("--workload", default="bert_base_layer")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 64 MiB device copy (reference for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE runs of this script)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -73,6 +99,13 @@ def main():
         nm.nm_encoder_layer(desc, x, yq, None, ws)
 
     nm.nm_encoder_layer(desc, x, yq, None, ws, taps=taps)  # fills the buffers the per-kernel timings read
+
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.int8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # a plain copy kernel of known size: reads 64 MiB, writes 64 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -153,7 +186,8 @@ def main():
         else:
             ach, peak, unit = work / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
         kernels.append(dict(kernel=name, bound=bound, ms=round(ms, 5), achieved=round(ach, 2),
-                            peak=peak, unit=unit, frac=round(ach / peak, 4)))
+                            peak=peak, unit=unit, frac=round(ach / peak, 4),
+                            traffic=pmc_traffic_bytes(name) if args.workload == "bert_base_layer" else None))
     # the HBM-bound row kernels again at shapes beyond the last-level cache (the softmax shape is
     # that of the 12-layer BERT-base workload: 16 x 12 x 512 rows of 512 scores)
     big = []
@@ -178,7 +212,7 @@ def main():
     del xl, ol, sl, pl, fl, fo
     dom = max(kernels, key=lambda k: k["ms"])
     roofline = dict(bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"], unit=dom["unit"],
-                    frac=dom["frac"], traffic=None, kernel=dom["kernel"],
+                    frac=dom["frac"], traffic=dom["traffic"], kernel=dom["kernel"],
                     note="int8 MFMA rate in TOP/s (2 ops per multiply-accumulate)")
     gemm_ops = sum(2.0 * M * n * k for n, k in ((3 * H, H), (H, H), (F, H), (H, F)))
     gemm_ms = sum(k["ms"] for k in kernels if k["bound"] == "mfma")
