@@ -230,7 +230,7 @@ int32_t nm_attn_context(const int8_t* p, const int8_t* qkv, int32_t B, int32_t S
  * results bit-identical to nm_attn_scores -> nm_softmax_pwl -> nm_attn_context; the int32 scores
  * and the int8 probabilities stay in registers.  scores_out / p_out (device, [B,heads,S,S]) may be
  * NULL; when given they receive the intermediate tensors.
- * Limits: head size H / heads == 64, S <= 256, qkv 16-byte aligned, H % 16 == 0; other shapes
+ * Limits: head size H / heads == 64, S <= 512, qkv 16-byte aligned, H % 16 == 0; other shapes
  * return NM_ERR_UNSUPPORTED and the caller uses the three separate calls.
  * --------------------------------------------------------------------------------------------- */
 int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int32_t H, int32_t heads,

@@ -1,5 +1,5 @@
 // Fused attention for gfx950: scores = Q K^T, softmax-PWL, context = P V in one kernel, per
-// (batch, head, block of 128 queries).  The int32 scores and the int8 probabilities never leave
+// (batch, head, block of 64 queries).  The int32 scores and the int8 probabilities never leave
 // registers (they are written out only when the caller asks for them).
 //
 // Paper basis: Section 3.1 (attention is a linear operation mapped to matrix products) and
@@ -7,16 +7,20 @@
 // entry points (nm_attn_scores, nm_softmax_pwl, nm_attn_context), including the normative order
 // of the row sum, so the results are bit-identical to the unfused path.
 //
-// Layout trick: a wavefront owns 32 queries.  K rows feed the MFMA's row operand and Q rows its
-// column operand, so lane (m, h) (m = query, h = lane / 32) ends with the scores of query m for
-// the keys 32*blk + 8*g + 4*h + e (blk = key block, g = 0..3, e = 0..3): groups of four
-// consecutive keys, which are exactly the 4-element groups of the normative row sum (accumulator
-// index 8*blk + 2*g + h).  The butterfly over accumulators is then: in-register adds over blk
-// (masks 32, 16, 8), over g (masks 4, 2) and one cross-lane add with lane ^ 32 (mask 1).
-// The int8 probabilities are packed in place, four per register, and that register quadruple IS
-// the operand of the second product: the contraction index of an integer MFMA may be permuted
-// freely as long as both operands use the same permutation, so V^T is written to LDS with the key
-// order (blk, h, g, e) that matches the way the probabilities sit in the lanes.
+// Layout: a wavefront owns 16 queries and uses the 16x16x64 integer MFMA (one instruction covers
+// the whole head dimension).  K rows feed the row operand and Q rows the column operand, so lane
+// (m, hq) (m = lane % 16 = query, hq = lane / 16) ends with the scores of query m for the keys
+// 16*blk + 4*hq + e (blk = key block, e = 0..3): groups of four consecutive keys, which are the
+// 4-element groups of the normative row sum (accumulator index (4*blk + hq) % 64).  The butterfly
+// over accumulators is then: in-register adds over blk (masks 32, 16, 8, 4) and two cross-lane
+// adds (lane ^ 32 for mask 2, lane ^ 16 for mask 1).  Arithmetic dominates this kernel (about 20
+// vector instructions per score against 1/16 of an MFMA), so a wavefront of 16 queries costs
+// nothing in matrix throughput and gives the scheduler four times more, smaller units to balance
+// over the compute units than a 32x32 tiling would.
+// The int8 probabilities are packed in place, four per register, and four such registers ARE the
+// operand of the second product: the contraction index of an integer MFMA may be permuted freely
+// as long as both operands use the same permutation, so V^T is written to LDS with the key order
+// (64-key block, hq, blk % 4, e) that matches the way the probabilities sit in the lanes.
 #include <climits>
 
 #include "nm_device.h"
@@ -33,183 +37,225 @@ struct AttnParams {
     int8_t* p_out;        // optional [B, heads, S, S]
 };
 
-constexpr int kAttnThreads = 256;
+constexpr int kAttnThreads = 256;   // four wavefronts, 64 queries
 constexpr int kHeadDim = 64;
 
-__device__ __forceinline__ int attn_swz(int row) { return ((row >> 1) & 3) ^ ((row >> 2) & 3); }
-__device__ __forceinline__ int attn_koff(int row, int chunk) { return row * 64 + ((chunk ^ attn_swz(row)) << 4); }
+// K image: 64-byte rows, the four 16-byte chunks of a row rotated by (row / 4) % 4 so that the 16
+// lanes of an operand read (16 consecutive rows, one chunk) cover all banks.
+__device__ __forceinline__ int attn_koff(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); }
+// V^T image: one row per head column, SV bytes apart, plus 64 bytes after every 16 rows (spreads
+// the transposing writes over the banks).
+template <int SV>
+__device__ __forceinline__ int attn_voff(int col) { return col * SV + (col >> 4) * 64; }
 
-// kFull: S == 32 * NB, so no key or query is masked (removes every per-key predicate).
-template <int NB, bool kFull>
-__global__ __launch_bounds__(kAttnThreads) void attention_pwl_kernel(AttnParams p)
+constexpr size_t attn_lds_bytes(int nkb) { return (size_t)nkb * 64 * 64 + 64 * ((size_t)nkb * 64 + 16) + 4 * 64; }
+
+// 4x4 byte transpose: in[k] holds bytes (k, 0..3); out[c] holds bytes (0..3, c).
+__device__ __forceinline__ void transpose4x4(const unsigned in[4], unsigned out[4])
 {
-    constexpr int SK = NB * 32;   // padded key count
-    constexpr int SV = SK + 16;   // row stride of the transposed V image (bank spread)
-    __shared__ __attribute__((aligned(16))) int8_t sK[SK * 64];
-    __shared__ __attribute__((aligned(16))) int8_t sVt[kHeadDim * SV];
-    extern __shared__ float2 s_kb[];
+    const unsigned t0 = __builtin_amdgcn_perm(in[1], in[0], 0x05010400u);  // a0 b0 a1 b1
+    const unsigned t1 = __builtin_amdgcn_perm(in[3], in[2], 0x05010400u);  // c0 d0 c1 d1
+    const unsigned t2 = __builtin_amdgcn_perm(in[1], in[0], 0x07030602u);  // a2 b2 a3 b3
+    const unsigned t3 = __builtin_amdgcn_perm(in[3], in[2], 0x07030602u);  // c2 d2 c3 d3
+    out[0] = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
+    out[1] = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
+    out[2] = __builtin_amdgcn_perm(t3, t2, 0x05040100u);
+    out[3] = __builtin_amdgcn_perm(t3, t2, 0x07060302u);
+}
+
+// NKB: padded key count / 64.  kFull: S == 64 * NKB, so no key or query is masked (removes every
+// per-key predicate).
+template <int NKB, bool kFull>
+__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2))) void attention_pwl_kernel(AttnParams p)
+{
+    constexpr int SK = NKB * 64;   // padded key count
+    constexpr int NBLK = SK / 16;  // 16-key blocks
+    constexpr int SV = SK + 16;    // row stride of the transposed V image
+    extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+    int8_t* sK = smem;
+    int8_t* sVt = smem + SK * 64;
+    float2* s_kb = reinterpret_cast<float2*>(smem + attn_lds_bytes(NKB));
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int fr = lane & 31, h = lane >> 5;
+    const int fr = lane & 15, hq = lane >> 4;
     const int b = blockIdx.y / p.heads, head = blockIdx.y % p.heads;
-    const int S = kFull ? 32 * NB : p.S, H = p.H;
+    const int S = kFull ? SK : p.S, H = p.H;
     const long ld = 3L * H;
     const int8_t* __restrict__ base = p.qkv + (long)b * S * ld + head * kHeadDim;
 
     stage_table(s_kb, p.t_exp);
-    // K tile -> LDS (rows past S are zero), V tile -> LDS transposed with the key permutation
+    // K tile -> LDS (rows past S are zero)
     for (int idx = tid; idx < SK * 4; idx += kAttnThreads) {
         const int r = idx >> 2, c = idx & 3;
-        v4i kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-        if (r < S) {
-            kv = *reinterpret_cast<const v4i*>(base + (long)r * ld + H + 16 * c);
-            vv = *reinterpret_cast<const v4i*>(base + (long)r * ld + 2 * H + 16 * c);
-        }
+        v4i kv = {0, 0, 0, 0};
+        if (kFull || r < S) kv = *reinterpret_cast<const v4i*>(base + (long)r * ld + H + 16 * c);
         *reinterpret_cast<v4i*>(&sK[attn_koff(r, c)]) = kv;
-        const int pos = (r & ~31) + 16 * ((r >> 2) & 1) + 4 * ((r >> 3) & 3) + (r & 3);
+    }
+    // V tile -> LDS, transposed: a thread takes 4 keys x 16 head columns, transposes the bytes in
+    // registers and writes one dword (4 keys of one column) per column.  Key r sits at position
+    // 64*(r/64) + 16*((r/4)%4) + 4*((r/16)%4) + r%4 of its column's row.
+    for (int idx = tid; idx < SK; idx += kAttnThreads) {
+        const int r0 = (idx >> 2) * 4, c = idx & 3;
+        v4i vv[4];
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            sVt[(16 * c + e) * SV + pos] = (int8_t)((unsigned)vv[e >> 2] >> (8 * (e & 3)));
+        for (int k = 0; k < 4; ++k) {
+            vv[k] = v4i{0, 0, 0, 0};
+            if (kFull || r0 + k < S) vv[k] = *reinterpret_cast<const v4i*>(base + (long)(r0 + k) * ld + 2 * H + 16 * c);
+        }
+        const int pos = (r0 & ~63) + 16 * ((r0 >> 2) & 3) + 4 * ((r0 >> 4) & 3);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned in[4] = {(unsigned)vv[0][q], (unsigned)vv[1][q], (unsigned)vv[2][q], (unsigned)vv[3][q]};
+            unsigned out[4];
+            transpose4x4(in, out);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                *reinterpret_cast<unsigned*>(&sVt[attn_voff<SV>(16 * c + 4 * q + e) + pos]) = out[e];
+        }
     }
     // this lane's query row, straight from global memory into the MFMA operand registers
-    const int m = blockIdx.x * 128 + wave * 32 + fr;
-    v4i qf[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
-    if (m < S) {
-        qf[0] = *reinterpret_cast<const v4i*>(base + (long)m * ld + 16 * h);
-        qf[1] = *reinterpret_cast<const v4i*>(base + (long)m * ld + 32 + 16 * h);
-    }
+    const int m = blockIdx.x * 64 + wave * 16 + fr;
+    v4i qf = {0, 0, 0, 0};
+    if (kFull || m < S) qf = *reinterpret_cast<const v4i*>(base + (long)m * ld + 16 * hq);
     __syncthreads();
 
     // ---- scores ---------------------------------------------------------------------------------
-    v16i acc[NB];
+    v4i acc[NBLK];
 #pragma unroll
-    for (int blk = 0; blk < NB; ++blk) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[blk][v] = 0;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const v4i kf = *reinterpret_cast<const v4i*>(&sK[attn_koff(32 * blk + fr, 2 * ks + h)]);
-            acc[blk] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[ks], acc[blk], 0, 0, 0);
-        }
+    for (int blk = 0; blk < NBLK; ++blk) {
+        const v4i kf = *reinterpret_cast<const v4i*>(&sK[attn_koff(16 * blk + fr, hq)]);
+        acc[blk] = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
+        // keeps the operand reads of later blocks from piling up in registers
+        if ((blk & 3) == 3) __builtin_amdgcn_sched_barrier(0);
     }
     const long row_ss = ((long)blockIdx.y * S + m) * S;  // offset of this query's row in [B,heads,S,S]
     const bool vec4 = (S & 3) == 0;
-    if (p.scores_out && m < S) {
+    if (p.scores_out && (kFull || m < S)) {
 #pragma unroll
-        for (int blk = 0; blk < NB; ++blk)
+        for (int blk = 0; blk < NBLK; ++blk) {
+            const int key = 16 * blk + 4 * hq;
+            if (vec4 && (kFull || key < S)) {
+                *reinterpret_cast<v4i*>(p.scores_out + row_ss + key) = acc[blk];
+            } else {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int key = 32 * blk + 8 * g + 4 * h;
-                if (vec4 && key < S) {
-                    *reinterpret_cast<v4i*>(p.scores_out + row_ss + key) =
-                        v4i{acc[blk][4 * g], acc[blk][4 * g + 1], acc[blk][4 * g + 2], acc[blk][4 * g + 3]};
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (key + e < S) p.scores_out[row_ss + key + e] = acc[blk][4 * g + e];
-                }
+                for (int e = 0; e < 4; ++e)
+                    if (key + e < S) p.scores_out[row_ss + key + e] = acc[blk][e];
             }
+        }
     }
 
     // ---- softmax-PWL ----------------------------------------------------------------------------
     int mi = INT_MIN;
 #pragma unroll
-    for (int blk = 0; blk < NB; ++blk)
+    for (int blk = 0; blk < NBLK; ++blk)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int key = 32 * blk + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (kFull || key < S) mi = max(mi, acc[blk][v]);
-        }
+        for (int e = 0; e < 4; ++e)
+            if (kFull || 16 * blk + 4 * hq + e < S) mi = max(mi, acc[blk][e]);
     mi = max(mi, __shfl_xor(mi, 32, 64));
+    mi = max(mi, __shfl_xor(mi, 16, 64));
 
-    // exp values replace the scores in place (same registers, float bits)
-    float part[NB][4];
+    // exp values replace the scores in place (same registers, float bits).  Keys 256.. wrap onto
+    // the 64 accumulators of keys 0..255 (accumulator = (key / 4) % 64) and continue their sums.
+    constexpr int NP = NBLK < 16 ? NBLK : 16;
+    float part[NP];
 #pragma unroll
-    for (int blk = 0; blk < NB; ++blk)
+    for (int blk = 0; blk < NBLK; ++blk) {
+        float s = blk < 16 ? 0.0f : part[blk & 15];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            float s = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int key = 32 * blk + 8 * g + 4 * h + e;
-                float x = 0.0f;
-                if (kFull || key < S) {
-                    const float t = (float)(acc[blk][4 * g + e] - mi) * p.alpha_scores;
-                    int seg;
-                    x = pwl_eval(t, p.t_exp, s_kb, seg);
-                    s = s + x;
-                }
-                acc[blk][4 * g + e] = __float_as_int(x);
+        for (int e = 0; e < 4; ++e) {
+            float x = 0.0f;
+            if (kFull || 16 * blk + 4 * hq + e < S) {
+                const float t = (float)(acc[blk][e] - mi) * p.alpha_scores;
+                int seg;
+                x = pwl_eval(t, p.t_exp, s_kb, seg);
+                s = s + x;
             }
-            part[blk][g] = s;
+            acc[blk][e] = __float_as_int(x);
         }
-    // butterfly over the accumulator index 8*blk + 2*g + h: masks 32, 16, 8 (blk), 4, 2 (g), 1 (h)
+        part[blk & 15] = s;
+        // bounds the number of table look-ups in flight (each holds two registers)
+        if (NBLK > 16 && (blk & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+    }
+    // butterfly over the accumulator index 4*blk + hq: masks 32, 16, 8, 4 (blk), then 2, 1 (hq)
 #pragma unroll
-    for (int mask = NB / 2; mask >= 1; mask >>= 1)
+    for (int mask = NP / 2; mask >= 1; mask >>= 1)
 #pragma unroll
-        for (int blk = 0; blk < mask; ++blk)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) part[blk][g] = part[blk][g] + part[blk + mask][g];
-    const float s02 = part[0][0] + part[0][2];
-    const float s13 = part[0][1] + part[0][3];
-    const float sh = s02 + s13;
-    const float sum = sh + __shfl_xor(sh, 32, 64);
+        for (int blk = 0; blk < mask; ++blk) part[blk] = part[blk] + part[blk + mask];
+    float sum = part[0];
+    sum = sum + __shfl_xor(sum, 32, 64);
+    sum = sum + __shfl_xor(sum, 16, 64);
     int segr;
     const float r = pwl_eval(sum, p.t_recip, p.t_recip.kb, segr);
 
-    unsigned pk[NB][4];
+    unsigned pk[NBLK];
 #pragma unroll
-    for (int blk = 0; blk < NB; ++blk)
+    for (int blk = 0; blk < NBLK; ++blk) {
+        int q[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            int q[4];
+        for (int e = 0; e < 4; ++e)
+            q[e] = (kFull || 16 * blk + 4 * hq + e < S) ? requant(__int_as_float(acc[blk][e]) * r, p.inv_s_p) : 0;
+        pk[blk] = pack4(q[0], q[1], q[2], q[3]);
+    }
+    if (p.p_out && (kFull || m < S)) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int key = 32 * blk + 8 * g + 4 * h + e;
-                q[e] = (kFull || key < S) ? requant(__int_as_float(acc[blk][4 * g + e]) * r, p.inv_s_p) : 0;
+        for (int blk = 0; blk < NBLK; ++blk) {
+            const int key = 16 * blk + 4 * hq;
+            if (vec4 && (kFull || key < S)) {
+                *reinterpret_cast<unsigned*>(p.p_out + row_ss + key) = pk[blk];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (key + e < S) p.p_out[row_ss + key + e] = (int8_t)(pk[blk] >> (8 * e));
             }
-            pk[blk][g] = pack4(q[0], q[1], q[2], q[3]);
         }
-    if (p.p_out && m < S) {
-#pragma unroll
-        for (int blk = 0; blk < NB; ++blk)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int key = 32 * blk + 8 * g + 4 * h;
-                if (vec4 && key < S) {
-                    *reinterpret_cast<unsigned*>(p.p_out + row_ss + key) = pk[blk][g];
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (key + e < S) p.p_out[row_ss + key + e] = (int8_t)(pk[blk][g] >> (8 * e));
-                }
-            }
     }
 
     // ---- context --------------------------------------------------------------------------------
-    const long orow = ((long)b * S + m) * H + head * kHeadDim;
+    v4i a2[4];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        v16i a2;
+    for (int cb = 0; cb < 4; ++cb) a2[cb] = v4i{0, 0, 0, 0};
 #pragma unroll
-        for (int v = 0; v < 16; ++v) a2[v] = 0;
+    for (int kb = 0; kb < NKB; ++kb) {
+        const v4i pf = {(int)pk[4 * kb], (int)pk[4 * kb + 1], (int)pk[4 * kb + 2], (int)pk[4 * kb + 3]};
 #pragma unroll
-        for (int blk = 0; blk < NB; ++blk) {
-            const v4i vf = *reinterpret_cast<const v4i*>(&sVt[(32 * cb + fr) * SV + 32 * blk + 16 * h]);
-            const v4i pf = {(int)pk[blk][0], (int)pk[blk][1], (int)pk[blk][2], (int)pk[blk][3]};
-            a2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, a2, 0, 0, 0);
-        }
-        if (m < S) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                int q[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    q[e] = requant(__builtin_fmaf((float)a2[4 * g + e], p.alpha_ctx, 0.0f), p.inv_s_ctx);
-                *reinterpret_cast<unsigned*>(p.ctx + orow + 32 * cb + 8 * g + 4 * h) = pack4(q[0], q[1], q[2], q[3]);
-            }
+        for (int cb = 0; cb < 4; ++cb) {
+            const v4i vf = *reinterpret_cast<const v4i*>(&sVt[attn_voff<SV>(16 * cb + fr) + 64 * kb + 16 * hq]);
+            a2[cb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, a2[cb], 0, 0, 0);
         }
     }
+    if (kFull || m < S) {
+        const long orow = ((long)b * S + m) * H + head * kHeadDim;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+            int q[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                q[e] = requant(__builtin_fmaf((float)a2[cb][e], p.alpha_ctx, 0.0f), p.inv_s_ctx);
+            *reinterpret_cast<unsigned*>(p.ctx + orow + 16 * cb + 4 * hq) = pack4(q[0], q[1], q[2], q[3]);
+        }
+    }
+}
+
+template <int NKB>
+static int32_t launch_attention(const AttnParams& p, hipStream_t st)
+{
+    const size_t shmem = attn_lds_bytes(NKB) + sizeof(float2) * (size_t)p.t_exp.nseg;
+    static bool configured = false;  // one attribute call per instantiation pair
+    if (!configured) {
+        int32_t rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_pwl_kernel<NKB, true>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
+                               "hipFuncSetAttribute(attention_pwl_kernel)");
+        if (rc) return rc;
+        rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_pwl_kernel<NKB, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
+                       "hipFuncSetAttribute(attention_pwl_kernel)");
+        if (rc) return rc;
+        configured = true;
+    }
+    const dim3 grid((p.S + 63) / 64, p.B * p.heads);
+    if (p.S == 64 * NKB) hipLaunchKernelGGL((attention_pwl_kernel<NKB, true>), grid, dim3(kAttnThreads), shmem, st, p);
+    else hipLaunchKernelGGL((attention_pwl_kernel<NKB, false>), grid, dim3(kAttnThreads), shmem, st, p);
+    return NM_OK;
 }
 
 }  // namespace nm
@@ -230,7 +276,7 @@ extern "C" int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int
     rc = get_dev_table(tables, recip_idx, &p.t_recip, "nm_attention_pwl(recip)");
     if (rc) return rc;
     if (H / heads != kHeadDim) return fail(NM_ERR_UNSUPPORTED, "nm_attention_pwl: head size %d (only 64 is fused)", H / heads);
-    if (S > 256) return fail(NM_ERR_UNSUPPORTED, "nm_attention_pwl: S %d > 256 (use the three separate calls)", S);
+    if (S > 512) return fail(NM_ERR_UNSUPPORTED, "nm_attention_pwl: S %d > 512 (use the three separate calls)", S);
     if ((int64_t)B * heads > 65535) return fail(NM_ERR_UNSUPPORTED, "nm_attention_pwl: B * heads > 65535");
     if ((int64_t)B * S * 3 * H >= (1LL << 31)) return fail(NM_ERR_UNSUPPORTED, "nm_attention_pwl: B*S*3H >= 2^31");
     if (!aligned(qkv, 16) || H % 16 != 0 || !aligned(ctx, 4) || H % 4 != 0 || (scores_out && !aligned(scores_out, 16)) ||
@@ -239,18 +285,11 @@ extern "C" int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int
     p.qkv = qkv; p.B = B; p.S = S; p.H = H; p.heads = heads;
     p.alpha_scores = alpha_scores; p.inv_s_p = inv_s_p; p.alpha_ctx = alpha_ctx; p.inv_s_ctx = inv_s_ctx;
     p.ctx = ctx; p.scores_out = scores_out; p.p_out = p_out;
-    const dim3 grid((S + 127) / 128, B * heads);
-    const size_t shmem = sizeof(float2) * (size_t)p.t_exp.nseg;
     hipStream_t st = (hipStream_t)stream;
-#define NM_ATTN_LAUNCH(NBV)                                                                         \
-    do {                                                                                            \
-        if (S == 32 * NBV) hipLaunchKernelGGL((attention_pwl_kernel<NBV, true>), grid, dim3(kAttnThreads), shmem, st, p); \
-        else hipLaunchKernelGGL((attention_pwl_kernel<NBV, false>), grid, dim3(kAttnThreads), shmem, st, p);              \
-    } while (0)
-    if (S <= 32) NM_ATTN_LAUNCH(1);
-    else if (S <= 64) NM_ATTN_LAUNCH(2);
-    else if (S <= 128) NM_ATTN_LAUNCH(4);
-    else NM_ATTN_LAUNCH(8);
-#undef NM_ATTN_LAUNCH
+    if (S <= 64) rc = launch_attention<1>(p, st);
+    else if (S <= 128) rc = launch_attention<2>(p, st);
+    else if (S <= 256) rc = launch_attention<4>(p, st);
+    else rc = launch_attention<8>(p, st);
+    if (rc) return rc;
     return check_hip(hipGetLastError(), "nm_attention_pwl launch");
 }

@@ -14,12 +14,13 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 // Segment of x (paper Section 3.2: uniform segments, inputs outside the range use the edge
 // segments): one subtract, one multiply, clamp in float, floor.  After the clamp u >= 0, so the
-// float -> int conversion (which truncates) IS the floor.
+// float -> int conversion (which truncates) IS the floor.  The clamp is one median-of-three; for a
+// NaN it returns the smaller bound, 0, as fmin(fmax(NaN, 0), nseg - 1) does.
 __device__ __forceinline__ int seg_index(float x, float lo, float inv_w, int nseg)
 {
     float u = x - lo;
     u = u * inv_w;
-    u = __builtin_fminf(__builtin_fmaxf(u, 0.0f), (float)(nseg - 1));
+    u = __builtin_amdgcn_fmed3f(u, 0.0f, (float)(nseg - 1));
     return (int)u;
 }
 
@@ -37,17 +38,23 @@ __device__ __forceinline__ float pwl_eval(float x, const DevTable& t, const floa
 }
 
 // Symmetric int8 code: round-to-nearest-even of v * inv_scale, saturated to [-127, 127].
+// Returns a word whose LOW BYTE is the code (the other bytes are not meaningful): saturate first
+// (the bounds are integers and rounding is monotone, so clamp and round commute), then add
+// 1.5 * 2^23: at that magnitude one ulp is 1, so the fp32 addition itself rounds to the nearest
+// integer, ties to even, and the low mantissa bits are the two's-complement integer.  A NaN
+// saturates to -127 (the median-of-three returns the smaller bound).
 __device__ __forceinline__ int requant(float v, float inv_scale)
 {
-    float r = __builtin_rintf(v * inv_scale);
-    r = __builtin_fminf(__builtin_fmaxf(r, -127.0f), 127.0f);
-    return (int)r;
+    float r = __builtin_amdgcn_fmed3f(v * inv_scale, -127.0f, 127.0f);
+    return __float_as_int(r + 12582912.0f);
 }
 
+// Packs the low bytes of four words into one (a in byte 0).
 __device__ __forceinline__ unsigned pack4(int a, int b, int c, int d)
 {
-    return (unsigned)(a & 0xff) | ((unsigned)(b & 0xff) << 8) | ((unsigned)(c & 0xff) << 16) |
-           ((unsigned)(d & 0xff) << 24);
+    const unsigned lo = __builtin_amdgcn_perm((unsigned)b, (unsigned)a, 0x0c0c0400u);  // a0 b0 0 0
+    const unsigned hi = __builtin_amdgcn_perm((unsigned)d, (unsigned)c, 0x04000c0cu);  // 0 0 c0 d0
+    return lo | hi;
 }
 
 // Copy a table's {k, b} pairs into LDS (all threads of the block take part; the caller

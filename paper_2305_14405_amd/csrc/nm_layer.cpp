@@ -118,7 +118,7 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
     }
     // 2-4: attention.  One fused kernel when the shape allows it (the scores and probabilities then
     // stay in registers; the taps, if given, still receive them), else three kernels.
-    const bool fused = H / nh == 64 && S <= 256 && H % 16 == 0 && aligned(qkv, 16) && aligned(ctx, 4) &&
+    const bool fused = H / nh == 64 && S <= 512 && H % 16 == 0 && aligned(qkv, 16) && aligned(ctx, 4) &&
                        (!(taps && taps->scores) || aligned(taps->scores, 16)) && !unfused_attention();
     if (fused) {
         if ((rc = nm_attention_pwl(qkv, B, S, H, nh, d->alpha_scores, d->tables, d->exp_idx, d->recip_idx,

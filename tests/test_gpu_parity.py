@@ -302,7 +302,7 @@ def test_attention_scores_and_context(oracle, B, S, H, heads):
 
 
 @pytest.mark.parametrize("B,S,heads", [(1, 64, 2), (2, 128, 12), (1, 200, 1), (2, 33, 1), (1, 256, 2), (3, 7, 2),
-                                        (1, 100, 3)])
+                                        (1, 100, 3), (1, 512, 2), (1, 300, 1), (2, 449, 1), (1, 384, 1)])
 def test_fused_attention_matches_oracle_stages(oracle, B, S, heads):
     """nm_attention_pwl against scores (int64 einsum), the oracle's softmax-PWL and the oracle's
     requantisation of P V: scores, probabilities and context all bit-exact."""
@@ -339,7 +339,7 @@ def test_fused_attention_matches_oracle_stages(oracle, B, S, heads):
 def test_fused_attention_unsupported_shapes():
     dt = nm.nm_build_tables([("exp", -16.0, 0.0, 64), ("recip", 1.0, 64.0, 64)])
     x = torch.zeros((8 * 96 * 3,), dtype=torch.int8, device=DEV)
-    for (B, S, H, heads) in [(1, 8, 96, 3), (1, 300, 64, 1)]:
+    for (B, S, H, heads) in [(1, 8, 96, 3), (1, 513, 64, 1)]:
         with pytest.raises(nm.NmError) as ei:
             nm.nm_attention_pwl(x, B, S, H, heads, 1.0, dt, 0, 1, 1.0, 1.0, 1.0, x)
         assert ei.value.status == nm.NM_ERR_UNSUPPORTED
