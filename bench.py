@@ -1,10 +1,14 @@
 """Benchmark of the PWL int8 encoder layer on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_base_layer]
+                    [--layers L] [--nseg N]
 
 A step is one pass of the whole hot path (nm_encoder_layer: QKV GEMM, scores, softmax-PWL, context,
-output projection, LayerNorm-PWL, FFN1 + GELU-PWL, FFN2, LayerNorm-PWL) over one batch of seeded
-synthetic input that already sits in HBM.  Prints ONE JSON line: sequences/s, per-kernel roofline
+output projection, LayerNorm-PWL, FFN1 + GELU-PWL, FFN2, LayerNorm-PWL; with --layers L > 1 the
+L-layer stack, nm_encoder_stack) over one batch of seeded synthetic input that already sits in HBM.
+The 512-token workloads default to their stack depth (bert_base_s512: 12, bert_large_s512: 24);
+--nseg overrides the segment count of every table (the accuracy of the layer output against the
+oracle's true-function mode is then reported next to the throughput).  Prints ONE JSON line: sequences/s, per-kernel roofline
 figures measured live with HIP events on the launch stream, and the CPU oracle timed on the host
 cores over the same workload (a reported baseline, not a target).
 """
@@ -21,6 +25,14 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, published: 5.0 POP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, published: 8 TB/s
+# Plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s (one
+# operation per lane per clock; the published 157.3 TFLOP/s counts packed two-wide FMAs, which this
+# build does not emit).  The fused attention kernel is bound by it: per score the method's
+# definition needs 18 scalar operations (row max 1; subtract, convert, scale 3; segment index:
+# subtract, multiply, two-sided clamp, floor 5; k*t+b 1; row-sum add 1; e*r 1; requantisation:
+# multiply, round, two-sided clamp, convert 5; the look-up itself not counted).
+PEAK_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+ATTN_OPS_PER_SCORE = 18.0
 
 # HBM-side traffic per launch at the bert_base_layer shapes, from two rocprofv3 --pmc runs of this
 # script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch).  A plain 64 MiB device copy in the same
@@ -52,6 +64,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bert_base_layer")
+    ap.add_argument("--layers", type=int, default=0, help="stack depth (0: the workload's own)")
+    ap.add_argument("--nseg", type=int, default=0, help="segments per table (0: the workload's own)")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -73,16 +87,21 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = W.config(args.workload)
-    p = W.layer_params(args.workload, 0)
+    if args.nseg:
+        cfg["nseg"] = args.nseg
+    n_layers = args.layers or {"bert_base_s512": 12, "bert_large_s512": 24}.get(args.workload, 1)
+    stack = W.stack_params(args.workload, n_layers)
+    p = stack[0]
     B, S, H, nh, F = (cfg[k] for k in ("B", "S", "H", "heads", "F"))
     M, d = B * S, cfg["H"] // cfg["heads"]
     order = ("gelu", "exp", "recip", "rsqrt")
     specs = [W.table_ranges(cfg)[n] for n in order]
     tables = nm.nm_build_tables(specs)          # the library's own table builder
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)  # noqa: E731
-    devw = {n: t(p[n]) for n in nm.LAYER_PTRS}
-    desc = nm.make_layer_desc(p, devw, tables)
-    ws = torch.empty(nm.nm_encoder_layer_workspace(desc), dtype=torch.uint8, device=dev)
+    devws = [{n: t(q[n]) for n in nm.LAYER_PTRS} for q in stack]
+    descs = [nm.make_layer_desc(q, dw, tables) for q, dw in zip(stack, devws)]
+    devw, desc = devws[0], descs[0]
+    ws = torch.empty(nm.nm_encoder_stack_workspace(descs), dtype=torch.uint8, device=dev)
     x = t(p["x"])
     yq = torch.empty((M, H), dtype=torch.int8, device=dev)
     taps = dict(qkv=torch.empty((M, 3 * H), dtype=torch.int8, device=dev),
@@ -96,7 +115,10 @@ def main():
 
     def step():
         # the hot path proper: intermediates live in the workspace, nothing optional is written
-        nm.nm_encoder_layer(desc, x, yq, None, ws)
+        if n_layers == 1:
+            nm.nm_encoder_layer(desc, x, yq, None, ws)
+        else:
+            nm.nm_encoder_stack(descs, x, yq, None, ws)
 
     nm.nm_encoder_layer(desc, x, yq, None, ws, taps=taps)  # fills the buffers the per-kernel timings read
 
@@ -157,7 +179,7 @@ def main():
         ("qkv_gemm", "mfma", 2.0 * M * 3 * H * H,
          lambda: nm.nm_gemm_pwl(x, devw["Wqkv"], bias=devw["bqkv"], alpha=p["alpha_qkv"],
                                 out_inv_scale_vec=osv, out_q=taps["qkv"])),
-        ("attention_fused", "hbm", float(M * 3 * H + M * H),
+        ("attention_fused", "alu", float(B * nh * S * S),
          lambda: nm.nm_attention_pwl(taps["qkv"], B, S, H, nh, p["alpha_scores"], tables, 1, 2,
                                      p["inv_s_p"], p["alpha_ctx"], p["inv_s_ctx"], taps["ctx"])),
         ("softmax_pwl", "hbm", float(B * nh * S * S * 5),
@@ -183,6 +205,8 @@ def main():
         ms = timed(fn, args.kernel_reps)
         if bound == "mfma":
             ach, peak, unit = work / (ms * 1e-3) / 1e12, PEAK_INT8_TOPS, "TFLOP/s"
+        elif bound == "alu":
+            ach, peak, unit = work * ATTN_OPS_PER_SCORE / (ms * 1e-3) / 1e12, PEAK_VALU_TOPS, "Tops/s"
         else:
             ach, peak, unit = work / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
         kernels.append(dict(kernel=name, bound=bound, ms=round(ms, 5), achieved=round(ach, 2),
@@ -233,30 +257,50 @@ def main():
         from oracle import oracle as O
         oid = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
         ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3]) for n, s in zip(order, specs)}
-        n_layers, c0 = 0, time.perf_counter()
+        # bounded sample: whole batch for the 128-token layer, two sequences of layer 0 otherwise
+        # (sequences are independent, so a batch subset is the same computation on fewer rows)
+        b_sub = B if (n_layers == 1 and M * H <= 4096 * 768) else min(B, 2)
+        p_sub = dict(p, B=b_sub)
+        x_sub = np.ascontiguousarray(p["x"][:b_sub * S])
+        n_runs, c0 = 0, time.perf_counter()
         while True:
-            want = O.encoder_layer(p, ot, p["x"], want_taps=False)
-            n_layers += 1
-            if time.perf_counter() - c0 > 10.0 or n_layers >= 8:
+            want = O.encoder_layer(p_sub, ot, x_sub, want_taps=False)
+            n_runs += 1
+            if time.perf_counter() - c0 > 10.0 or n_runs >= 8:
                 break
-        cpu_s = (time.perf_counter() - c0) / n_layers
+        cpu_s = (time.perf_counter() - c0) / n_runs
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        cpu_baseline = dict(value=round(B / cpu_s, 3), unit="sequences/s", cores=cores, kind="oracle",
-                            sample=f"{n_layers} full {args.workload} layer(s), B={B} sequences each, "
-                                   f"{cpu_s:.2f} s per layer")
-        # the library built its own tables: compare with the oracle's layer (1 LSB allowance)
-        step()
+        sample = (f"{n_runs} run(s) of layer 0 of {args.workload} on {b_sub} of {B} sequences, "
+                  f"{cpu_s:.2f} s per run")
+        if n_layers > 1:
+            sample += f"; value = {b_sub} / ({n_layers} layers x {cpu_s:.2f} s), extrapolated linearly over layers"
+        cpu_baseline = dict(value=round(b_sub / (cpu_s * n_layers), 4), unit="sequences/s", cores=cores,
+                            kind="oracle", sample=sample)
+        # layer 0 on the GPU (library-built tables) against the oracle's layer 0 (oracle-built tables:
+        # may differ in the last bit), and against the oracle's true-function mode (same quantised
+        # network, exact GELU / exp / 1/x / rsqrt in binary64): the PWL approximation error
+        yq0 = torch.empty((M, H), dtype=torch.int8, device=dev)
+        yf0 = torch.empty((M, H), dtype=torch.float32, device=dev)
+        nm.nm_encoder_layer(desc, x, yq0, yf0, ws)
         torch.cuda.synchronize()
-        diff = np.abs(yq.cpu().numpy().astype(int) - want["y_q"].astype(int))
+        rows = b_sub * S
+        diff = np.abs(yq0[:rows].cpu().numpy().astype(int) - want["y_q"].astype(int))
+        exact, _ = O.encoder_layer_exact(p_sub, ot, x_sub, quantise=True)
+        err = np.abs(yf0[:rows].cpu().numpy().astype(np.float64) - exact)
         parity = dict(int8_max_abs_diff=int(diff.max()), int8_mismatch_frac=float((diff > 0).mean()),
-                      note="library-built tables vs oracle-built tables (may differ in the last bit)")
+                      note="layer 0, library-built tables vs oracle-built tables (may differ in the last bit)",
+                      pwl_vs_exact_f=dict(nseg=int(cfg["nseg"]), max_abs=float(err.max()),
+                                          mean_abs=float(err.mean()),
+                                          rel_rms=float(np.sqrt((err ** 2).mean() / (exact ** 2).mean())),
+                                          note="fp32 layer-0 output vs the oracle's true-function mode "
+                                               "of the same quantised layer"))
 
     out = dict(metric="PWL encoder-layer sequences/s + int8 MFMA util % + nonlinear-kernel HBM GB/s",
                value=round(seq_per_s, 1), unit="sequences/s", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True,
                scaling="weak", vs_baseline=None, dtype="int8 (int32 accumulate, fp32 epilogue)",
                data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
-                                             nseg=cfg["nseg"], layers=1),
+                                             nseg=cfg["nseg"], layers=n_layers),
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
                summary=summary,
                parity=parity)

@@ -304,6 +304,22 @@ int32_t nm_encoder_layer_workspace(const nm_layer_desc* desc, size_t* bytes);
 int32_t nm_encoder_layer(const nm_layer_desc* desc, const int8_t* x, int8_t* y_q, float* y_f32,
                          void* ws, size_t ws_bytes, const nm_layer_taps* taps, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * nm_encoder_stack: n_layers encoder layers back to back on one stream (the paper's Section 4
+ * models are stacks of identical layers: 12 for BERT-base, 24 for BERT-large).  Layer l reads the
+ * int8 output of layer l-1, so descs[l].resid1_scale / alpha_qkv must be formed from layer l-1's
+ * output scale (the caller's job, as for every other multiplier).  All layers share B, S and H;
+ * F and the tables may differ per layer.
+ * descs: HOST array of n_layers descriptors (read during the call only).  x, y_q, y_f32 as for
+ * nm_encoder_layer (y_f32 is the last layer's fp32 output).  If only y_f32 is given and
+ * n_layers > 1 the intermediate layers still produce int8.  The workspace holds two activation
+ * buffers plus the largest per-layer workspace; query it first.  Nothing is allocated and the
+ * host does not wait for the GPU.
+ * --------------------------------------------------------------------------------------------- */
+int32_t nm_encoder_stack_workspace(const nm_layer_desc* descs, int32_t n_layers, size_t* bytes);
+int32_t nm_encoder_stack(const nm_layer_desc* descs, int32_t n_layers, const int8_t* x, int8_t* y_q,
+                         float* y_f32, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

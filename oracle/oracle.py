@@ -337,6 +337,16 @@ def encoder_layer(p: dict, tables: dict, x, want_taps: bool = True):
     return out
 
 
+def encoder_stack(params: list, tables: dict, x):
+    """Layers applied one after the other: layer l reads the int8 output of layer l-1 (the paper's
+    Section 4 models are stacks of identical encoder layers).  Returns the last layer's outputs."""
+    out = None
+    for p in params:
+        out = encoder_layer(p, tables, x, want_taps=False)
+        x = out["y_q"]
+    return out
+
+
 ABSMAX_NAMES = ("x", "q", "k", "v", "p", "ctx", "ln1", "ffn1", "out", "gelu_in_min", "gelu_in_max",
                 "softmax_den_max", "var_eps_max")
 

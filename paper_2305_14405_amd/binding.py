@@ -22,7 +22,8 @@ NM_DT_I32, NM_DT_F32 = 0, 1
 EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_tables",
            "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_destroy",
            "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_pwl_apply", "nm_attn_scores",
-           "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer")
+           "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer",
+           "nm_encoder_stack_workspace", "nm_encoder_stack")
 
 
 class NmError(RuntimeError):
@@ -116,6 +117,9 @@ def load(preload_torch: bool = True) -> C.CDLL:
     L.nm_encoder_layer_workspace.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_size_t)]
     L.nm_encoder_layer.argtypes = [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.POINTER(LayerTaps), C.c_void_p]
+    L.nm_encoder_stack_workspace.argtypes = [C.POINTER(LayerDesc), C.c_int32, C.POINTER(C.c_size_t)]
+    L.nm_encoder_stack.argtypes = [C.POINTER(LayerDesc), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_size_t, C.c_void_p]
     _lib = L
     return L
 
@@ -318,3 +322,22 @@ def nm_encoder_layer(desc: LayerDesc, x, y_q, y_f32, ws, taps: dict | None = Non
     nbytes = ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes
     _check(load().nm_encoder_layer(C.byref(desc), _ptr(x), _ptr(y_q), _ptr(y_f32), _ptr(ws), nbytes,
                                    C.byref(ct) if ct is not None else None, _stream(stream)))
+
+
+def _desc_array(descs):
+    arr = (LayerDesc * len(descs))()
+    for i, d in enumerate(descs):
+        C.memmove(C.byref(arr, i * C.sizeof(LayerDesc)), C.byref(d), C.sizeof(LayerDesc))
+    return arr
+
+
+def nm_encoder_stack_workspace(descs) -> int:
+    n = C.c_size_t()
+    _check(load().nm_encoder_stack_workspace(_desc_array(descs), len(descs), C.byref(n)))
+    return n.value
+
+
+def nm_encoder_stack(descs, x, y_q, y_f32, ws, stream=None, ws_bytes=None):
+    nbytes = ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes
+    _check(load().nm_encoder_stack(_desc_array(descs), len(descs), _ptr(x), _ptr(y_q), _ptr(y_f32),
+                                   _ptr(ws), nbytes, _stream(stream)))

@@ -172,4 +172,62 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
                             nullptr, stream);
 }
 
+// ---- stack of layers -------------------------------------------------------------------------
+
+static int32_t validate_stack(const nm_layer_desc* descs, int32_t n_layers, const char* what, size_t* layer_ws)
+{
+    if (!descs) return fail(NM_ERR_INVALID_ARG, "%s: descs is NULL", what);
+    if (n_layers < 1) return fail(NM_ERR_INVALID_ARG, "%s: n_layers %d < 1", what, n_layers);
+    size_t need = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        int32_t rc = validate_layer(&descs[l], what);
+        if (rc) return rc;
+        if (descs[l].B != descs[0].B || descs[l].S != descs[0].S || descs[l].H != descs[0].H)
+            return fail(NM_ERR_INVALID_ARG, "%s: layer %d has another B, S or H than layer 0", what, l);
+        const size_t t = plan_layer(&descs[l]).total;
+        if (t > need) need = t;
+    }
+    *layer_ws = need;
+    return NM_OK;
+}
+
+int32_t nm_encoder_stack_workspace(const nm_layer_desc* descs, int32_t n_layers, size_t* bytes)
+{
+    size_t layer_ws = 0;
+    int32_t rc = validate_stack(descs, n_layers, "nm_encoder_stack_workspace", &layer_ws);
+    if (rc) return rc;
+    if (!bytes) return fail(NM_ERR_INVALID_ARG, "nm_encoder_stack_workspace: bytes is NULL");
+    const size_t act = round_up((size_t)descs[0].B * descs[0].S * descs[0].H, 256);
+    *bytes = layer_ws + 2 * act;
+    return NM_OK;
+}
+
+int32_t nm_encoder_stack(const nm_layer_desc* descs, int32_t n_layers, const int8_t* x, int8_t* y_q,
+                         float* y_f32, void* ws, size_t ws_bytes, void* stream)
+{
+    size_t layer_ws = 0;
+    int32_t rc = validate_stack(descs, n_layers, "nm_encoder_stack", &layer_ws);
+    if (rc) return rc;
+    if (!x) return fail(NM_ERR_INVALID_ARG, "nm_encoder_stack: x is NULL");
+    if (!y_q && !y_f32) return fail(NM_ERR_INVALID_ARG, "nm_encoder_stack: no output");
+    const size_t act = round_up((size_t)descs[0].B * descs[0].S * descs[0].H, 256);
+    if (!ws) return fail(NM_ERR_WORKSPACE, "nm_encoder_stack: workspace is NULL");
+    if (!aligned(ws, 256)) return fail(NM_ERR_WORKSPACE, "nm_encoder_stack: workspace not 256-byte aligned");
+    if (ws_bytes < layer_ws + 2 * act)
+        return fail(NM_ERR_WORKSPACE, "nm_encoder_stack: workspace %zu bytes < %zu needed", ws_bytes, layer_ws + 2 * act);
+    // two activation buffers in front of the per-layer workspace; layer l writes buffer l % 2
+    char* w = static_cast<char*>(ws);
+    int8_t* act_buf[2] = {reinterpret_cast<int8_t*>(w), reinterpret_cast<int8_t*>(w + act)};
+    void* lws = w + 2 * act;
+    const int8_t* in = x;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const bool last = l == n_layers - 1;
+        int8_t* out = last ? y_q : act_buf[l & 1];
+        if ((rc = nm_encoder_layer(&descs[l], in, out, last ? y_f32 : nullptr, lws, ws_bytes - 2 * act, nullptr, stream)))
+            return rc;
+        in = out;
+    }
+    return NM_OK;
+}
+
 }  // extern "C"

@@ -144,6 +144,22 @@ def layer_params(name: str, seed: int = 0) -> dict:
     return with_scales(layer_tensors(config(name), seed), stored_scales(name, seed))
 
 
+def stack_params(name: str, n_layers: int) -> list:
+    """A stack of ``n_layers`` layers of a named workload: layer l has its own weights (seed l) and
+    reads the int8 output of layer l-1, so its input scale is that layer's output scale.  The
+    activation scales are the calibrated ones of layer 0 for every layer (each layer's input is a
+    LayerNorm output with the same statistics).  Element 0 also carries the stack input ``x``."""
+    cfg, act = config(name), stored_scales(name, 0)
+    out = []
+    for l in range(n_layers):
+        t = layer_tensors(cfg, l)
+        if l > 0:
+            del t["x"]
+            t["s_x"] = act["out"]
+        out.append(with_scales(t, act))
+    return out
+
+
 # ---------------------------------------------------------------------------------------------
 # Inputs for the single-kernel tests and for the stress distribution (values that sweep the whole
 # table range, fall outside it, sit on break points, constant rows).

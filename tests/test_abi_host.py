@@ -129,5 +129,20 @@ def test_compute_entry_points_validate_before_launch(lib):
     need = M * 3 * H + SS * 4 + SS + M * H + M * H * 4 + M * H + M * F + M * H * 4
     assert need <= n.value <= need + 8 * 256
     assert lib.nm_encoder_layer(C.byref(ld), one, one, None, one, n, None, z) == nm.NM_ERR_INVALID_ARG
+    # stack: two activation buffers on top of the largest layer workspace; layers must agree on B, S, H
+    arr = (nm.LayerDesc * 3)()
+    for i in range(3):
+        arr[i].B, arr[i].S, arr[i].H, arr[i].heads, arr[i].F = 32, 128, 768, 12, 3072 if i != 1 else 1024
+    ns = C.c_size_t()
+    assert lib.nm_encoder_stack_workspace(arr, 3, C.byref(ns)) == nm.NM_OK
+    assert ns.value == n.value + 2 * M * H
+    assert lib.nm_encoder_stack_workspace(arr, 0, C.byref(ns)) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_encoder_stack_workspace(None, 3, C.byref(ns)) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_encoder_stack(arr, 3, None, one, None, one, ns, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_encoder_stack(arr, 3, one, None, None, one, ns, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_encoder_stack(arr, 3, one, one, None, None, ns, z) == nm.NM_ERR_WORKSPACE
+    arr[2].S = 64
+    assert lib.nm_encoder_stack_workspace(arr, 3, C.byref(ns)) == nm.NM_ERR_INVALID_ARG
+    assert b"layer 2" in lib.nm_last_error()
     ld.heads = 7
     assert lib.nm_encoder_layer_workspace(C.byref(ld), C.byref(n)) == nm.NM_ERR_INVALID_ARG

@@ -390,6 +390,46 @@ def test_encoder_layer_all_stages(oracle, name):
         assert_f32_close(got[k], want[k], f"{name} layer {k}")
 
 
+@pytest.mark.parametrize("name", ["bert_base_s512", "bert_large_s512"])
+def test_encoder_layer_s512_full_size(oracle, name):
+    """The 512-token layers of the 12- and 24-layer workloads at full size (fused attention with
+    wrapped row-sum accumulators): every stage exact."""
+    want, got = run_layer(oracle, name)
+    for k in ("qkv", "scores", "p", "ctx", "ln1", "ffn1", "y_q"):
+        assert_exact(got[k], want[k], f"{name} layer {k}")
+    for k in ("attn", "ffn2", "y_f32"):
+        assert_f32_close(got[k], want[k], f"{name} layer {k}")
+
+
+@pytest.mark.parametrize("name,n_layers", [("tiny", 3), ("ragged", 2), ("bert_base_layer", 2)])
+def test_encoder_stack(oracle, name, n_layers):
+    """nm_encoder_stack against the oracle's layers applied one after the other."""
+    cfg = W.config(name)
+    ps = W.stack_params(name, n_layers)
+    specs = [W.table_ranges(cfg)[n] for n in ("gelu", "exp", "recip", "rsqrt")]
+    ot, dt = both_tables(oracle, specs)
+    want = oracle.encoder_stack(ps, dict(zip(("gelu", "exp", "recip", "rsqrt"), ot)), ps[0]["x"])
+    keep, descs = [], []
+    for p in ps:
+        devw = {n: dev(p[n]) for n in nm.LAYER_PTRS}
+        keep.append(devw)
+        descs.append(nm.make_layer_desc(p, devw, dt))
+    M, H = cfg["B"] * cfg["S"], cfg["H"]
+    ws = torch.empty(nm.nm_encoder_stack_workspace(descs), dtype=torch.uint8, device=DEV)
+    yq = torch.empty((M, H), dtype=torch.int8, device=DEV)
+    yf = torch.empty((M, H), dtype=torch.float32, device=DEV)
+    nm.nm_encoder_stack(descs, dev(ps[0]["x"]), yq, yf, ws)
+    assert_exact(host(yq), want["y_q"], f"{name} x{n_layers} stack output")
+    assert_f32_close(host(yf), want["y_f32"], f"{name} x{n_layers} stack fp32 output")
+    # fp32 output only
+    yf2 = torch.empty_like(yf)
+    nm.nm_encoder_stack(descs, dev(ps[0]["x"]), None, yf2, ws)
+    assert_f32_close(host(yf2), want["y_f32"], "stack, fp32 output only")
+    with pytest.raises(nm.NmError) as ei:
+        nm.nm_encoder_stack(descs, dev(ps[0]["x"]), yq, None, ws, ws_bytes=ws.numel() - 1)
+    assert ei.value.status == nm.NM_ERR_WORKSPACE
+
+
 def test_encoder_layer_with_library_built_tables(oracle):
     """The product path builds its own tables (host code of the library).  They may differ from
     the oracle's in the last bit, so int8 outputs are compared to within one code."""
