@@ -35,6 +35,7 @@ struct AttnParams {
     int8_t* ctx;
     int32_t* scores_out;  // optional [B, heads, S, S]
     int8_t* p_out;        // optional [B, heads, S, S]
+    int ctx_vec16;        // ctx is 16-byte aligned: context rows leave as 16-byte stores
 };
 
 constexpr int kAttnThreads = 256;   // four wavefronts, 64 queries
@@ -78,7 +79,21 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 15, hq = lane >> 4;
-    const int b = blockIdx.y / p.heads, head = blockIdx.y % p.heads;
+    // Workgroups are dealt to the eight XCDs round-robin by linear id.  Renumber them so that an
+    // XCD receives consecutive (head, query block) pairs: the query blocks of a head share its K
+    // and V, and neighbouring heads share 128-byte lines (a head's rows are 64-byte halves), so
+    // these fetches then meet in one L2 instead of going to memory once per XCD.
+    int bx = blockIdx.x, by = blockIdx.y;
+    {
+        const int total = gridDim.x * gridDim.y;
+        if ((total & 7) == 0) {
+            const int lin = blockIdx.x + gridDim.x * blockIdx.y;
+            const int v = (lin & 7) * (total >> 3) + (lin >> 3);
+            bx = v % gridDim.x;
+            by = v / gridDim.x;
+        }
+    }
+    const int b = by / p.heads, head = by % p.heads;
     const int S = kFull ? SK : p.S, H = p.H;
     const long ld = 3L * H;
     const int8_t* __restrict__ base = p.qkv + (long)b * S * ld + head * kHeadDim;
@@ -114,7 +129,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
         }
     }
     // this lane's query row, straight from global memory into the MFMA operand registers
-    const int m = blockIdx.x * 64 + wave * 16 + fr;
+    const int m = bx * 64 + wave * 16 + fr;
     v4i qf = {0, 0, 0, 0};
     if (kFull || m < S) qf = *reinterpret_cast<const v4i*>(base + (long)m * ld + 16 * hq);
     __syncthreads();
@@ -128,7 +143,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
         // keeps the operand reads of later blocks from piling up in registers
         if ((blk & 3) == 3) __builtin_amdgcn_sched_barrier(0);
     }
-    const long row_ss = ((long)blockIdx.y * S + m) * S;  // offset of this query's row in [B,heads,S,S]
+    const long row_ss = ((long)by * S + m) * S;  // offset of this query's row in [B,heads,S,S]
     const bool vec4 = (S & 3) == 0;
     if (p.scores_out && (kFull || m < S)) {
 #pragma unroll
@@ -219,19 +234,29 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
         const v4i pf = {(int)pk[4 * kb], (int)pk[4 * kb + 1], (int)pk[4 * kb + 2], (int)pk[4 * kb + 3]};
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
-            const v4i vf = *reinterpret_cast<const v4i*>(&sVt[attn_voff<SV>(16 * cb + fr) + 64 * kb + 16 * hq]);
+            // product cb takes the head columns 16*(row/4) + 4*cb + row%4, so that lane (m, hq)
+            // collects columns 16*hq .. 16*hq+15 over the four products: one 16-byte store
+            const v4i vf = *reinterpret_cast<const v4i*>(
+                &sVt[attn_voff<SV>(16 * (fr >> 2) + 4 * cb + (fr & 3)) + 64 * kb + 16 * hq]);
             a2[cb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, a2[cb], 0, 0, 0);
         }
     }
     if (kFull || m < S) {
         const long orow = ((long)b * S + m) * H + head * kHeadDim;
+        v4i o;
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
             int q[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 q[e] = requant(__builtin_fmaf((float)a2[cb][e], p.alpha_ctx, 0.0f), p.inv_s_ctx);
-            *reinterpret_cast<unsigned*>(p.ctx + orow + 16 * cb + 4 * hq) = pack4(q[0], q[1], q[2], q[3]);
+            o[cb] = (int)pack4(q[0], q[1], q[2], q[3]);
+        }
+        if (p.ctx_vec16) {
+            *reinterpret_cast<v4i*>(p.ctx + orow + 16 * hq) = o;
+        } else {
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) *reinterpret_cast<int*>(p.ctx + orow + 16 * hq + 4 * cb) = o[cb];
         }
     }
 }
@@ -285,6 +310,7 @@ extern "C" int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int
     p.qkv = qkv; p.B = B; p.S = S; p.H = H; p.heads = heads;
     p.alpha_scores = alpha_scores; p.inv_s_p = inv_s_p; p.alpha_ctx = alpha_ctx; p.inv_s_ctx = inv_s_ctx;
     p.ctx = ctx; p.scores_out = scores_out; p.p_out = p_out;
+    p.ctx_vec16 = aligned(ctx, 16) ? 1 : 0;
     hipStream_t st = (hipStream_t)stream;
     if (S <= 64) rc = launch_attention<1>(p, st);
     else if (S <= 128) rc = launch_attention<2>(p, st);
