@@ -173,6 +173,8 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
     // the 64 accumulators of keys 0..255 (accumulator = (key / 4) % 64) and continue their sums.
     constexpr int NP = NBLK < 16 ? NBLK : 16;
     float part[NP];
+    const float clo = p.t_exp.clamp_input ? p.t_exp.lo : -__builtin_inff();
+    const float chi = p.t_exp.clamp_input ? p.t_exp.hi : __builtin_inff();
 #pragma unroll
     for (int blk = 0; blk < NBLK; ++blk) {
         float s = blk < 16 ? 0.0f : part[blk & 15];
@@ -181,8 +183,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
             float x = 0.0f;
             if (kFull || 16 * blk + 4 * hq + e < S) {
                 const float t = (float)(acc[blk][e] - mi) * p.alpha_scores;
-                int seg;
-                x = pwl_eval(t, p.t_exp, s_kb, seg);
+                x = pwl_eval_bounded(t, clo, chi, p.t_exp, s_kb);
                 s = s + x;
             }
             acc[blk][e] = __float_as_int(x);
@@ -294,6 +295,8 @@ extern "C" int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int
 {
     if (!qkv || !ctx) return fail(NM_ERR_INVALID_ARG, "nm_attention_pwl: NULL pointer");
     if (B < 1 || S < 1 || H < 1 || heads < 1) return fail(NM_ERR_INVALID_ARG, "nm_attention_pwl: dimensions must be >= 1");
+    if (!(alpha_scores == alpha_scores) || __builtin_isinf(alpha_scores))
+        return fail(NM_ERR_INVALID_ARG, "nm_attention_pwl: alpha_scores must be finite");
     if (H % heads != 0) return fail(NM_ERR_INVALID_ARG, "nm_attention_pwl: H %d not divisible by heads %d", H, heads);
     AttnParams p{};
     int32_t rc = get_dev_table(tables, exp_idx, &p.t_exp, "nm_attention_pwl(exp)");

@@ -37,6 +37,26 @@ __device__ __forceinline__ float pwl_eval(float x, const DevTable& t, const floa
     return __builtin_fmaf(e.x, x, e.y);
 }
 
+// The same for a value that cannot be NaN (an int32 accumulator times finite multipliers): the
+// clamp flag is folded into the bounds (clo, chi = lo, hi with the flag, -inf, +inf without), so no
+// select is needed; identical results for every non-NaN x.
+__device__ __forceinline__ float pwl_eval_bounded(float x, float clo, float chi, const DevTable& t,
+                                                  const float2* kb)
+{
+    x = __builtin_amdgcn_fmed3f(x, clo, chi);
+    const int seg = seg_index(x, t.lo, t.inv_w, t.nseg);
+    const float2 e = kb[seg];
+    return __builtin_fmaf(e.x, x, e.y);
+}
+
+// Without the clamp flag.
+__device__ __forceinline__ float pwl_eval_noclamp(float x, const DevTable& t, const float2* kb, int& seg)
+{
+    seg = seg_index(x, t.lo, t.inv_w, t.nseg);
+    const float2 e = kb[seg];
+    return __builtin_fmaf(e.x, x, e.y);
+}
+
 // Symmetric int8 code: round-to-nearest-even of v * inv_scale, saturated to [-127, 127].
 // Returns a word whose LOW BYTE is the code (the other bytes are not meaningful): saturate first
 // (the bounds are integers and rounding is monotone, so clamp and round commute), then add

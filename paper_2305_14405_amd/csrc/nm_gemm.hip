@@ -180,7 +180,7 @@ __device__ __forceinline__ void epi_math(const GemmParams& p, const float2* s_kb
     for (int e = 0; e < 4; ++e) {
         float v = __builtin_fmaf((float)a4[e], c.scale[e], c.bias[e]);
         if (use_resid) v = __builtin_fmaf((float)r4[e], rs, v);
-        if (use_table) v = pwl_eval(v, p.table, s_kb, o.s[e]);
+        if (use_table) v = kEpi == EPI_Q_TABLE ? pwl_eval_noclamp(v, p.table, s_kb, o.s[e]) : pwl_eval(v, p.table, s_kb, o.s[e]);
         o.y[e] = v;
         if (need_q) o.q[e] = requant(v, c.inv[e]);
     }
@@ -750,7 +750,8 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     int epi = EPI_GENERIC;
     if (!g.alpha_vec && !g.out_inv_scale_vec && !g.dbg_seg) {
         const bool only_q = g.out_q && !g.out_f32 && !g.out_acc;
-        if (only_q && !g.resid) epi = g.has_table ? EPI_Q_TABLE : EPI_Q;
+        // EPI_Q_TABLE is compiled without the input clamp; a table with that flag takes the generic epilogue
+        if (only_q && !g.resid) epi = !g.has_table ? EPI_Q : g.table.clamp_input ? EPI_GENERIC : EPI_Q_TABLE;
         else if (g.out_f32 && !g.out_q && !g.out_acc && g.resid && !g.has_table && p.vec_out) epi = EPI_F32_RESID;
         else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
     }

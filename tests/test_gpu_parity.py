@@ -245,6 +245,22 @@ def test_gemm_per_column_scales_no_table(oracle, M, N, K):
     assert_f32_close(host(of), r["y"], "gemm per-column fp32")
 
 
+@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("M,N,K", [(256, 384, 128), (128, 1536, 256), (100, 130, 64)])
+def test_gemm_int8_only_table_out_of_range(oracle, M, N, K, flags):
+    """int8-only output (the specialised table epilogue) with pre-activations far outside the
+    table range, with and without the input-clamp flag."""
+    ot, dt = both_tables(oracle, [("gelu", -2.0, 2.0, 32)], flags=flags)
+    d = W.gemm_inputs(M, N, K, seed=3 + M, full_range=False)
+    alpha = float(np.float32(40.0 / (20 * 20 * np.sqrt(K))))
+    r = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, table=ot[0], out_inv_scale=9.0)
+    assert (r["seg"] == 0).mean() > 0.05 and (r["seg"] == 31).mean() > 0.05
+    oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=dt, table_idx=0,
+                   out_inv_scale=9.0, out_q=oq)
+    assert_exact(host(oq), r["q"], f"gemm int8-only, table flags {flags}")
+
+
 def test_gemm_extreme_operands(oracle):
     """All-(-127) x all-(+127) at the largest K of the workloads: |acc| = K * 127^2 > 2^24."""
     M, N, K = 40, 72, 3072
@@ -334,6 +350,32 @@ def test_fused_attention_matches_oracle_stages(oracle, B, S, heads):
     ctx2 = torch.empty_like(ctx)
     nm.nm_attention_pwl(dev(qkv), B, S, H, heads, alpha_s, dt, 0, 1, inv_p, alpha_c, inv_c, ctx2)
     assert_exact(host(ctx2), want_ctx, "fused context, no taps")
+
+
+@pytest.mark.parametrize("S", [128, 200])
+def test_fused_attention_clamp_flag_exp_table(oracle, S):
+    """Exp table with the input-clamp flag and scores far below the table range."""
+    B, heads, H = 2, 2, 128
+    ot, dt = both_tables(oracle, [("exp", -4.0, 0.0, 32), ("recip", 1.0, float(S), 64)], flags=1)
+    g = np.random.default_rng(S)
+    qkv = np.clip(np.rint(30 * g.standard_normal((B * S, 3 * H))), -127, 127).astype(np.int8)
+    q4 = qkv[:, :H].reshape(B, S, heads, 64).astype(np.int64)
+    k4 = qkv[:, H:2 * H].reshape(B, S, heads, 64).astype(np.int64)
+    v4 = qkv[:, 2 * H:].reshape(B, S, heads, 64).astype(np.int64)
+    scores = np.einsum("bihc,bjhc->bhij", q4, k4)
+    alpha_s, inv_p = float(np.float32(1.5e-3)), float(np.float32(127.0))
+    sm = oracle.softmax_pwl(scores.reshape(-1, S).astype(np.int32), alpha_s, ot[0], ot[1], inv_p)
+    assert (sm["seg_exp"] == 0).mean() > 0.2
+    P = sm["q"].reshape(B, heads, S, S)
+    cacc = np.einsum("bhij,bjhc->bihc", P.astype(np.int64), v4).reshape(B * S, H)
+    alpha_c, inv_c = float(np.float32(2.0e-3)), float(np.float32(1.7))
+    cv = (cacc.astype(np.float32) * np.float32(alpha_c)).astype(np.float32)
+    want_ctx = np.clip(np.rint((cv * np.float32(inv_c)).astype(np.float32)), -127, 127).astype(np.int8)
+    ctx = torch.empty((B * S, H), dtype=torch.int8, device=DEV)
+    pp = torch.empty((B, heads, S, S), dtype=torch.int8, device=DEV)
+    nm.nm_attention_pwl(dev(qkv), B, S, H, heads, alpha_s, dt, 0, 1, inv_p, alpha_c, inv_c, ctx, None, pp)
+    assert_exact(host(pp), P, "fused probabilities, clamped exp input")
+    assert_exact(host(ctx), want_ctx, "fused context, clamped exp input")
 
 
 def test_fused_attention_unsupported_shapes():
