@@ -20,6 +20,7 @@
 // k of one row.  The same k of A and W always meet in the same (lane group, byte) slot, and int32
 // addition is exact, so results do not depend on tiling, on the k order or on any split of K.
 #include <cstdlib>
+#include <type_traits>
 
 #include "nm_device.h"
 
@@ -606,71 +607,79 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_k
     // Row blocks outermost: as soon as a block of 32 rows is finished its int8 rows are read back
     // from the patch and stored, so the stores of one block overlap the arithmetic of the next
     // (the patch rows of a block are written and read by the same wavefront: no workgroup barrier).
+    // The body exists twice: for a tile that lies wholly inside the output (and vector-aligned
+    // outputs) every bounds test is a compile-time constant, which leaves straight-line code whose
+    // table look-ups the scheduler can batch; edge tiles take the guarded copy.
+    auto finish_rows = [&](auto full_c) {
+        constexpr bool kFullTile = decltype(full_c)::value;
 #pragma unroll
-    for (int i = 0; i < TMF; ++i) {
-        const int prow = 32 * (row_blk0 + i) + frag_row;  // row inside the sub-tile
-        const int m = m0 + wave_m + prow;
-        const long rowoff = obase + (long)m * p.ldo;
+        for (int i = 0; i < TMF; ++i) {
+            const int prow = 32 * (row_blk0 + i) + frag_row;  // row inside the sub-tile
+            const int m = m0 + wave_m + prow;
+            const long rowoff = obase + (long)m * p.ldo;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+            for (int j = 0; j < TN; ++j) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int cl = wave_n + 32 * j + 8 * g + 4 * frag_half;  // column inside the tile
-                const int nb = n0 + cl;
-                if (nb >= p.N || m >= p.M) continue;
-                const bool vec = p.vec_out && nb + 3 < p.N;
-                Col4 c;
-                {
-                    const v4f sc = *reinterpret_cast<const v4f*>(s_cols + cl);
-                    const v4f bi = *reinterpret_cast<const v4f*>(s_cols + BN + cl);
-                    const v4f iv = *reinterpret_cast<const v4f*>(s_cols + 2 * BN + cl);
+                for (int g = 0; g < 4; ++g) {
+                    const int cl = wave_n + 32 * j + 8 * g + 4 * frag_half;  // column inside the tile
+                    const int nb = n0 + cl;
+                    if (!kFullTile && (nb >= p.N || m >= p.M)) continue;
+                    const bool vec = kFullTile || (p.vec_out && nb + 3 < p.N);
+                    Col4 c;
+                    {
+                        const v4f sc = *reinterpret_cast<const v4f*>(s_cols + cl);
+                        const v4f bi = *reinterpret_cast<const v4f*>(s_cols + BN + cl);
+                        const v4f iv = *reinterpret_cast<const v4f*>(s_cols + 2 * BN + cl);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { c.scale[e] = sc[e]; c.bias[e] = bi[e]; c.inv[e] = iv[e]; }
-                }
-                int a4[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) a4[e] = fin[i][j][4 * g + e];
-                int r4[4] = {0, 0, 0, 0};
-                if (kEpi == EPI_F32_RESID) {
-                    if (nb + 3 < p.N) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) r4[e] = (int)(int8_t)(resw[i][j][g] >> (8 * e));
-                    } else {
-                        load_resid4(p, rowoff, nb, false, r4);
+                        for (int e = 0; e < 4; ++e) { c.scale[e] = sc[e]; c.bias[e] = bi[e]; c.inv[e] = iv[e]; }
                     }
-                } else if (kEpi == EPI_GENERIC && p.resid) {
-                    load_resid4(p, rowoff, nb, vec, r4);
-                }
-                Epi4 o;
-                epi_math<kEpi>(p, s_kb, a4, c, r4, o);
-                epi_store<kEpi>(p, rowoff, nb, a4, o, vec, patch_q);
-                if (patch_q)
-                    *reinterpret_cast<unsigned*>(patch + prow * SW + 32 * j + 8 * g + 4 * frag_half) =
-                        pack4(o.q[0], o.q[1], o.q[2], o.q[3]);
-            }
-        }
-        if (patch_q) {
-            // same wavefront wrote these 32 patch rows: order its LDS writes before its reads
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            constexpr int PCPR = WN / 16;  // 16-byte chunks per patch row
-            for (int c = lane; c < 32 * PCPR; c += 64) {
-                const int row = 32 * (row_blk0 + i) + c / PCPR, cc = c % PCPR;
-                const int mr = m0 + wave_m + row, n = n0 + wave_n + 16 * cc;
-                if (mr < p.M && n < p.N) {
-                    const v4i v = *reinterpret_cast<const v4i*>(patch + row * SW + 16 * cc);
-                    int8_t* dst = p.out_q + obase + (long)mr * p.ldo + n;
-                    if (n + 15 < p.N) {
-                        *reinterpret_cast<v4i*>(dst) = v;
-                    } else {
-                        for (int b = 0; b < 16 && n + b < p.N; ++b)
-                            dst[b] = (int8_t)((unsigned)v[b >> 2] >> (8 * (b & 3)));
+                    int a4[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a4[e] = fin[i][j][4 * g + e];
+                    int r4[4] = {0, 0, 0, 0};
+                    if (kEpi == EPI_F32_RESID) {
+                        if (kFullTile || nb + 3 < p.N) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) r4[e] = (int)(int8_t)(resw[i][j][g] >> (8 * e));
+                        } else {
+                            load_resid4(p, rowoff, nb, false, r4);
+                        }
+                    } else if (kEpi == EPI_GENERIC && p.resid) {
+                        load_resid4(p, rowoff, nb, vec, r4);
                     }
+                    Epi4 o;
+                    epi_math<kEpi>(p, s_kb, a4, c, r4, o);
+                    epi_store<kEpi>(p, rowoff, nb, a4, o, vec, patch_q);
+                    if (patch_q)
+                        *reinterpret_cast<unsigned*>(patch + prow * SW + 32 * j + 8 * g + 4 * frag_half) =
+                            pack4(o.q[0], o.q[1], o.q[2], o.q[3]);
                 }
             }
+            if (patch_q) {
+                // same wavefront wrote these 32 patch rows: order its LDS writes before its reads
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                constexpr int PCPR = WN / 16;  // 16-byte chunks per patch row
+                for (int c = lane; c < 32 * PCPR; c += 64) {
+                    const int row = 32 * (row_blk0 + i) + c / PCPR, cc = c % PCPR;
+                    const int mr = m0 + wave_m + row, n = n0 + wave_n + 16 * cc;
+                    if (kFullTile || (mr < p.M && n < p.N)) {
+                        const v4i v = *reinterpret_cast<const v4i*>(patch + row * SW + 16 * cc);
+                        int8_t* dst = p.out_q + obase + (long)mr * p.ldo + n;
+                        if (kFullTile || n + 15 < p.N) {
+                            *reinterpret_cast<v4i*>(dst) = v;
+                        } else {
+                            for (int b = 0; b < 16 && n + b < p.N; ++b)
+                                dst[b] = (int8_t)((unsigned)v[b >> 2] >> (8 * (b & 3)));
+                        }
+                    }
+                }
+            }
         }
-    }
+    };
+    if (m0 + BM <= p.M && n0 + BN <= p.N && p.vec_out) finish_rows(std::true_type{});
+    else finish_rows(std::false_type{});
 }
 
 template <int BM, int BN, int WM, int WN>
