@@ -98,7 +98,9 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
     const long ld = 3L * H;
     const int8_t* __restrict__ base = p.qkv + (long)b * S * ld + head * kHeadDim;
 
+    float2* s_kb_recip = s_kb + p.t_exp.nseg;
     stage_table(s_kb, p.t_exp);
+    stage_table(s_kb_recip, p.t_recip);
     // K tile -> LDS (rows past S are zero)
     for (int idx = tid; idx < SK * 4; idx += kAttnThreads) {
         const int r = idx >> 2, c = idx & 3;
@@ -201,7 +203,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
     sum = sum + __shfl_xor(sum, 32, 64);
     sum = sum + __shfl_xor(sum, 16, 64);
     int segr;
-    const float r = pwl_eval(sum, p.t_recip, p.t_recip.kb, segr);
+    const float r = pwl_eval(sum, p.t_recip, s_kb_recip, segr);
 
     unsigned pk[NBLK];
 #pragma unroll
@@ -265,7 +267,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
 template <int NKB>
 static int32_t launch_attention(const AttnParams& p, hipStream_t st)
 {
-    const size_t shmem = attn_lds_bytes(NKB) + sizeof(float2) * (size_t)p.t_exp.nseg;
+    const size_t shmem = attn_lds_bytes(NKB) + sizeof(float2) * ((size_t)p.t_exp.nseg + (size_t)p.t_recip.nseg);
     static bool configured = false;  // one attribute call per instantiation pair
     if (!configured) {
         int32_t rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_pwl_kernel<NKB, true>),

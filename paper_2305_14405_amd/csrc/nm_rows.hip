@@ -97,8 +97,12 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
     float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
     uint16_t* __restrict__ seg_exp, uint16_t* __restrict__ seg_recip)
 {
+    // both tables in LDS (the per-row reciprocal look-up would otherwise add one more global-memory
+    // round trip to every row's dependency chain)
     extern __shared__ float2 s_kb[];
+    float2* s_kb_recip = s_kb + t_exp.nseg;
     stage_table(s_kb, t_exp);
+    stage_table(s_kb_recip, t_recip);
     __syncthreads();
     constexpr int kRowsPerWave = 64 / G;
     constexpr int kRowsPerBlock = kRowsPerWave * (kRowThreads / 64);
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
         }
         const float S = group_sum<G>(part);
         int sr;
-        const float r = pwl_eval(S, t_recip, t_recip.kb, sr);
+        const float r = pwl_eval(S, t_recip, s_kb_recip, sr);
         if (seg_recip && live && g == 0) seg_recip[row] = (uint16_t)sr;
         // ---- scale + store -------------------------------------------------------------------
 #pragma unroll
@@ -222,6 +226,12 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
     const int lane = threadIdx.x & 63;
     const int g = lane % G;
     const int sub = (threadIdx.x >> 6) * kRowsPerWave + lane / G;
+    // The rsqrt table goes to LDS while the first row is on its way from memory (staged after the
+    // row's loads are issued; every thread of a block makes the same number of trips, so the
+    // barrier inside the first trip is reached by all): the look-up then costs an LDS access
+    // instead of a second global-memory round trip in each row's dependency chain.
+    extern __shared__ float2 s_kb[];
+    bool staged = false;
 
     for (long row0 = (long)blockIdx.x * kRowsPerBlock; row0 < rows;
          row0 += (long)gridDim.x * kRowsPerBlock) {
@@ -254,6 +264,11 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
             for (int q = 0; q < 4; ++q)
                 if (ok[c][q]) part = part + x[c][q];
         }
+        if (!staged) {
+            stage_table(s_kb, t);
+            __syncthreads();
+            staged = true;
+        }
         const float mu = group_sum<G>(part) * inv_L;
         float part2 = 0.0f;
 #pragma unroll
@@ -267,7 +282,7 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
         const float var = group_sum<G>(part2) * inv_L;
         const float u = var + eps;
         int sr;
-        const float r = pwl_eval(u, t, t.kb, sr);
+        const float r = pwl_eval(u, t, s_kb, sr);
         if (seg && live && g == 0) seg[row] = (uint16_t)sr;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
@@ -358,7 +373,7 @@ int32_t launch_softmax(const void* in, int32_t in_dtype, float alpha, int64_t ro
     if (rs.C < 0) return fail(NM_ERR_UNSUPPORTED, "softmax: cols %d not supported", cols);
     const bool vec = cols % 4 == 0 && aligned(in, 16) && (!out_f32 || aligned(out_f32, 16)) &&
                      (!out_q || aligned(out_q, 4)) && (!seg_exp || aligned(seg_exp, 8));
-    const size_t shmem = sizeof(float2) * (size_t)t_exp.nseg;
+    const size_t shmem = sizeof(float2) * ((size_t)t_exp.nseg + (size_t)t_recip.nseg);
     bool ok;
     const bool i32 = in_dtype == NM_DT_I32;
     if (i32 && vec) ok = launch_softmax_t<true, true>(rs, dim3(), shmem, stream, in, alpha, rows, cols, t_exp, t_recip, out_inv_scale, out_q, out_f32, seg_exp, seg_recip);
@@ -378,7 +393,8 @@ static bool launch_layernorm_t(RowShape rs, hipStream_t stream, const float* in,
     if (rs.G == GG && rs.C == CC) {                                                                 \
         constexpr int rpb = (64 / GG) * (kRowThreads / 64);                                         \
         hipLaunchKernelGGL((layernorm_pwl_kernel<GG, CC, kVec>), dim3(blocks_for(rows, rpb)),       \
-                           dim3(kRowThreads), 0, stream, in, gamma, beta, eps, inv_L, rows, cols, t, \
+                           dim3(kRowThreads), sizeof(float2) * (size_t)t.nseg, stream, in, gamma, beta, \
+                           eps, inv_L, rows, cols, t,                                               \
                            ois, oq, of, seg);                                                       \
         return true;                                                                                \
     }
