@@ -18,18 +18,59 @@ namespace nm {
 
 constexpr int kRowThreads = 256;
 
-template <typename T>
-__device__ __forceinline__ T shfl_xor(T v, int mask)
+// One butterfly step: op(v, value of lane ^ MASK), without going through LDS.  Masks 1 and 2 are
+// quad permutes, 4 and 8 compositions of the row mirrors (lane ^ 7 ^ 3, lane ^ 15 ^ 7), 16 and 32
+// the gfx950 row / half swaps: swapping a register with a copy of itself leaves {even rows twice}
+// in one and {odd rows twice} in the other (halves likewise), and op is commutative, so
+// op(first, second) is op(v, partner) in every lane.
+template <int MASK, typename Op>
+__device__ __forceinline__ int butterfly_step(int v, Op op)
 {
-    return __shfl_xor(v, mask, 64);
+    if (MASK == 1) return op(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false));
+    if (MASK == 2) return op(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false));
+    if (MASK == 4) {
+        const int t = __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false);   // lane ^ 7
+        return op(v, __builtin_amdgcn_update_dpp(0, t, 0x1B, 0xf, 0xf, false));     // ... ^ 3
+    }
+    if (MASK == 8) {
+        const int t = __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, false);   // lane ^ 15
+        return op(v, __builtin_amdgcn_update_dpp(0, t, 0x141, 0xf, 0xf, false));    // ... ^ 7
+    }
+    if (MASK == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+        return op((int)r[0], (int)r[1]);
+    }
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return op((int)r[0], (int)r[1]);
+}
+
+struct AddF32 {
+    __device__ __forceinline__ int operator()(int a, int b) const { return __float_as_int(__int_as_float(a) + __int_as_float(b)); }
+};
+struct MaxF32 {
+    __device__ __forceinline__ int operator()(int a, int b) const { return __float_as_int(__builtin_fmaxf(__int_as_float(a), __int_as_float(b))); }
+};
+struct MaxI32 {
+    __device__ __forceinline__ int operator()(int a, int b) const { return max(a, b); }
+};
+
+// Butterfly over the G lanes that own a row, partner masks G/2 ... 1 in that order.
+template <int G, typename Op>
+__device__ __forceinline__ int group_reduce(int v, Op op)
+{
+    if (G > 32) v = butterfly_step<32>(v, op);
+    if (G > 16) v = butterfly_step<16>(v, op);
+    if (G > 8) v = butterfly_step<8>(v, op);
+    if (G > 4) v = butterfly_step<4>(v, op);
+    if (G > 2) v = butterfly_step<2>(v, op);
+    if (G > 1) v = butterfly_step<1>(v, op);
+    return v;
 }
 
 template <int G>
 __device__ __forceinline__ float group_sum(float v)
 {
-#pragma unroll
-    for (int mask = G / 2; mask >= 1; mask >>= 1) v = v + shfl_xor(v, mask);
-    return v;
+    return __int_as_float(group_reduce<G>(__float_as_int(v), AddF32{}));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -91,7 +132,11 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
 // Softmax-PWL.  G lanes own a row (G = 64 for rows longer than 128 elements); a lane owns the
 // 4-element groups g, g + G, ... (C of them).
 // ------------------------------------------------------------------------------------------
-template <int G, int C, bool kI32, bool kVec>
+// kFull: cols == 4 * G * C (every lane's groups are inside the row; implies kVec).  Rows past
+// the end are then computed on a copy of the last row and only their stores are masked, so the
+// whole body is straight-line code: no per-element predicates, and the table look-ups of a row
+// are issued together instead of one per basic block.
+template <int G, int C, bool kI32, bool kVec, bool kFull>
 __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
     const void* __restrict__ in, float alpha, long rows, int cols, DevTable t_exp, DevTable t_recip,
     float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
@@ -114,7 +159,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
          row0 += (long)gridDim.x * kRowsPerBlock) {
         const long row = row0 + sub;
         const bool live = row < rows;
-        const long base = row * (long)cols;
+        const long base = (kFull && !live ? rows - 1 : row) * (long)cols;
         float e[C][4];
         bool ok[C][4];
         int ai[C][4];
@@ -125,7 +170,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
         for (int c = 0; c < C; ++c) {
             const int j0 = 4 * (g + G * c);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) ok[c][q] = live && (j0 + q) < cols;
+            for (int q = 0; q < 4; ++q) ok[c][q] = kFull || (live && (j0 + q) < cols);
             if (kVec) {
                 if (ok[c][0]) {  // cols % 4 == 0: a group is all in or all out
                     if (kI32) {
@@ -153,11 +198,8 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
                     else mf = __builtin_fmaxf(mf, e[c][q]);
                 }
         }
-#pragma unroll
-        for (int mask = G / 2; mask >= 1; mask >>= 1) {
-            if (kI32) mi = max(mi, shfl_xor(mi, mask));
-            else mf = __builtin_fmaxf(mf, shfl_xor(mf, mask));
-        }
+        if (kI32) mi = group_reduce<G>(mi, MaxI32{});
+        else mf = __int_as_float(group_reduce<G>(__float_as_int(mf), MaxF32{}));
         // ---- exp + canonical sum ------------------------------------------------------------
         float part = 0.0f;
         int se[C][4];
@@ -191,7 +233,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
                 qv[q] = requant(p[q], out_inv_scale);
             }
             if (kVec) {
-                if (ok[c][0]) {
+                if (kFull ? live : ok[c][0]) {
                     if (out_f32) *reinterpret_cast<v4f*>(out_f32 + base + j0) = v4f{p[0], p[1], p[2], p[3]};
                     if (out_q) *reinterpret_cast<unsigned*>(out_q + base + j0) = pack4(qv[0], qv[1], qv[2], qv[3]);
                     if (seg_exp)
@@ -215,7 +257,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
 // ------------------------------------------------------------------------------------------
 // LayerNorm-PWL.  Same ownership as softmax.
 // ------------------------------------------------------------------------------------------
-template <int G, int C, bool kVec>
+template <int G, int C, bool kVec, bool kFull>
 __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
     const float* __restrict__ in, const float* __restrict__ gamma, const float* __restrict__ beta,
     float eps, float inv_L, long rows, int cols, DevTable t, float out_inv_scale,
@@ -237,7 +279,7 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
          row0 += (long)gridDim.x * kRowsPerBlock) {
         const long row = row0 + sub;
         const bool live = row < rows;
-        const long base = row * (long)cols;
+        const long base = (kFull && !live ? rows - 1 : row) * (long)cols;
         float x[C][4];
         bool ok[C][4];
         float part = 0.0f;
@@ -246,7 +288,7 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
             const int j0 = 4 * (g + G * c);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                ok[c][q] = live && (j0 + q) < cols;
+                ok[c][q] = kFull || (live && (j0 + q) < cols);
                 x[c][q] = 0.0f;
             }
             if (kVec) {
@@ -290,7 +332,7 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
             float y[4];
             int qv[4];
             if (kVec) {
-                if (ok[c][0]) {
+                if (kFull ? live : ok[c][0]) {
                     v4f ga = *reinterpret_cast<const v4f*>(gamma + j0);
                     v4f be = *reinterpret_cast<const v4f*>(beta + j0);
 #pragma unroll
@@ -351,9 +393,14 @@ static bool launch_softmax_t(RowShape rs, dim3 grid_hint, size_t shmem, hipStrea
 #define NM_SM_CASE(GG, CC)                                                                          \
     if (rs.G == GG && rs.C == CC) {                                                                 \
         constexpr int rpb = (64 / GG) * (kRowThreads / 64);                                         \
-        hipLaunchKernelGGL((softmax_pwl_kernel<GG, CC, kI32, kVec>), dim3(blocks_for(rows, rpb)),   \
-                           dim3(kRowThreads), shmem, stream, in, alpha, rows, cols, te, tr, ois, oq, \
-                           of, se, sr);                                                             \
+        if (kVec && cols == 4 * GG * CC)                                                            \
+            hipLaunchKernelGGL((softmax_pwl_kernel<GG, CC, kI32, kVec, kVec>),                      \
+                               dim3(blocks_for(rows, rpb)), dim3(kRowThreads), shmem, stream, in,   \
+                               alpha, rows, cols, te, tr, ois, oq, of, se, sr);                     \
+        else                                                                                        \
+            hipLaunchKernelGGL((softmax_pwl_kernel<GG, CC, kI32, kVec, false>),                     \
+                               dim3(blocks_for(rows, rpb)), dim3(kRowThreads), shmem, stream, in,   \
+                               alpha, rows, cols, te, tr, ois, oq, of, se, sr);                     \
         return true;                                                                                \
     }
     NM_SM_CASE(1, 1) NM_SM_CASE(2, 1) NM_SM_CASE(4, 1) NM_SM_CASE(8, 1) NM_SM_CASE(16, 1)
@@ -392,10 +439,14 @@ static bool launch_layernorm_t(RowShape rs, hipStream_t stream, const float* in,
 #define NM_LN_CASE(GG, CC)                                                                          \
     if (rs.G == GG && rs.C == CC) {                                                                 \
         constexpr int rpb = (64 / GG) * (kRowThreads / 64);                                         \
-        hipLaunchKernelGGL((layernorm_pwl_kernel<GG, CC, kVec>), dim3(blocks_for(rows, rpb)),       \
-                           dim3(kRowThreads), sizeof(float2) * (size_t)t.nseg, stream, in, gamma, beta, \
-                           eps, inv_L, rows, cols, t,                                               \
-                           ois, oq, of, seg);                                                       \
+        if (kVec && cols == 4 * GG * CC)                                                            \
+            hipLaunchKernelGGL((layernorm_pwl_kernel<GG, CC, kVec, kVec>), dim3(blocks_for(rows, rpb)), \
+                               dim3(kRowThreads), sizeof(float2) * (size_t)t.nseg, stream, in, gamma, \
+                               beta, eps, inv_L, rows, cols, t, ois, oq, of, seg);                  \
+        else                                                                                        \
+            hipLaunchKernelGGL((layernorm_pwl_kernel<GG, CC, kVec, false>), dim3(blocks_for(rows, rpb)), \
+                               dim3(kRowThreads), sizeof(float2) * (size_t)t.nseg, stream, in, gamma, \
+                               beta, eps, inv_L, rows, cols, t, ois, oq, of, seg);                  \
         return true;                                                                                \
     }
     NM_LN_CASE(1, 1) NM_LN_CASE(2, 1) NM_LN_CASE(4, 1) NM_LN_CASE(8, 1) NM_LN_CASE(16, 1)
