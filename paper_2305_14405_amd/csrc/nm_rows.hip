@@ -89,8 +89,8 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
     const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (kVec) {
         const long ngroups = n / 4;
-        for (long gidx = tid; gidx < ngroups; gidx += nthreads) {
-            float x[4];
+        // one group of four elements: load, scale, PWL, requantise, store
+        auto load_group = [&](long gidx, float (&x)[4]) {
             if (in_is_i32) {
                 v4i a = reinterpret_cast<const v4i*>(in)[gidx];
 #pragma unroll
@@ -100,6 +100,8 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
 #pragma unroll
                 for (int e = 0; e < 4; ++e) x[e] = a[e] * alpha;
             }
+        };
+        auto finish_group = [&](long gidx, const float (&x)[4]) {
             float y[4];
             int s[4], q[4];
 #pragma unroll
@@ -113,6 +115,21 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
                 reinterpret_cast<uint2*>(dbg_seg)[gidx] =
                     make_uint2((unsigned)s[0] | ((unsigned)s[1] << 16),
                                (unsigned)s[2] | ((unsigned)s[3] << 16));
+        };
+        // four groups per trip: their loads are issued together (more bytes in flight per lane)
+        constexpr int kUnroll = 4;
+        long gidx = tid;
+        for (; gidx + (kUnroll - 1) * nthreads < ngroups; gidx += kUnroll * nthreads) {
+            float x[kUnroll][4];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) load_group(gidx + u * nthreads, x[u]);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) finish_group(gidx + u * nthreads, x[u]);
+        }
+        for (; gidx < ngroups; gidx += nthreads) {
+            float x[4];
+            load_group(gidx, x);
+            finish_group(gidx, x);
         }
     }
     // scalar path: everything when !kVec, the (< 4 element) tail otherwise
