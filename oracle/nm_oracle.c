@@ -519,6 +519,128 @@ int nmo_gemm_pwl(const nmo_gemm* g)
 }
 
 /* ------------------------------------------------------------------------------------------- */
+/* int8 convolution (NHWC) with the same fused epilogue, and the two pooling operators of a    */
+/* residual CNN.                                                                                */
+/* ------------------------------------------------------------------------------------------- */
+
+typedef struct {
+    int32_t B, H, W, Cin;        /* input  x: int8 [B, H, W, Cin] (channels contiguous) */
+    int32_t Cout, kh, kw;        /* weight w: int8 [Cout, kh, kw, Cin] */
+    int32_t stride, pad;         /* same in both directions; padding is the zero code */
+    const int8_t* x;
+    const int8_t* w;
+    const float* bias;           /* [Cout] or NULL */
+    const float* alpha_vec;      /* [Cout] per-channel scale (a folded batch normalisation), or NULL -> alpha */
+    float alpha;
+    const int8_t* resid;         /* [B, Ho, Wo, Cout] int8 residual or NULL */
+    float resid_scale;
+    const nmo_table* table;      /* NULL -> no nonlinearity */
+    float out_inv_scale;
+    int8_t* out_q;               /* [B, Ho, Wo, Cout]; any output may be NULL */
+    float* out_f32;
+    int32_t* out_acc;
+} nmo_conv;
+
+/*
+ * Section 3.1: a convolution is a linear operation whose matrix form has one row per output
+ * position and one column per output channel; written here as its direct definition,
+ *   acc[b,ho,wo,n] = sum_{i<kh, j<kw, c<Cin} x[b, ho*stride - pad + i, wo*stride - pad + j, c] * w[n,i,j,c]
+ * (positions outside the image contribute nothing), exact in int32, followed by the epilogue of
+ * the matrix product: v = fmaf((float)acc, alpha_n, bias_n); residual; PWL; requantise.
+ * Ho = (H + 2 pad - kh) / stride + 1, Wo likewise.
+ */
+int nmo_conv2d_pwl(const nmo_conv* g)
+{
+    if (!g || !g->x || !g->w || g->B < 0 || g->H < 1 || g->W < 1 || g->Cin < 1 || g->Cout < 1 ||
+        g->kh < 1 || g->kw < 1 || g->stride < 1 || g->pad < 0)
+        return NMO_ERR_ARG;
+    if (g->H + 2 * g->pad < g->kh || g->W + 2 * g->pad < g->kw) return NMO_ERR_ARG;
+    const int32_t Ho = (g->H + 2 * g->pad - g->kh) / g->stride + 1;
+    const int32_t Wo = (g->W + 2 * g->pad - g->kw) / g->stride + 1;
+    const int64_t rows = (int64_t)g->B * Ho * Wo;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const int32_t wo = (int32_t)(r % Wo), ho = (int32_t)((r / Wo) % Ho), b = (int32_t)(r / ((int64_t)Wo * Ho));
+        for (int32_t n = 0; n < g->Cout; ++n) {
+            int32_t acc = 0;
+            for (int32_t i = 0; i < g->kh; ++i) {
+                const int32_t hi = ho * g->stride - g->pad + i;
+                if (hi < 0 || hi >= g->H) continue;
+                for (int32_t j = 0; j < g->kw; ++j) {
+                    const int32_t wi = wo * g->stride - g->pad + j;
+                    if (wi < 0 || wi >= g->W) continue;
+                    const int8_t* xp = g->x + (((size_t)b * g->H + hi) * g->W + wi) * g->Cin;
+                    const int8_t* wp = g->w + (((size_t)n * g->kh + i) * g->kw + j) * g->Cin;
+                    for (int32_t c = 0; c < g->Cin; ++c) acc += (int32_t)xp[c] * (int32_t)wp[c];
+                }
+            }
+            const size_t o = (size_t)r * g->Cout + n;
+            if (g->out_acc) g->out_acc[o] = acc;
+            float v = fmaf((float)acc, g->alpha_vec ? g->alpha_vec[n] : g->alpha, g->bias ? g->bias[n] : 0.0f);
+            if (g->resid) v = fmaf((float)g->resid[o], g->resid_scale, v);
+            if (g->table) {
+                int32_t s;
+                v = pwl_eval(v, g->table, &s);
+            }
+            if (g->out_f32) g->out_f32[o] = v;
+            if (g->out_q) g->out_q[o] = requant(v, g->out_inv_scale);
+        }
+    }
+    return NMO_OK;
+}
+
+/*
+ * Max pooling over k x k windows (stride, zero-free padding: positions outside the image are
+ * left out of the maximum).  The paper does not discuss pooling; the maximum of int8 codes that
+ * share one scale is exact and order-free, so it is taken directly on the codes.
+ * x: int8 [B, H, W, C] -> y: int8 [B, Ho, Wo, C].
+ */
+int nmo_maxpool_i8(const int8_t* x, int32_t B, int32_t H, int32_t W, int32_t C, int32_t k,
+                   int32_t stride, int32_t pad, int8_t* y)
+{
+    if (!x || !y || B < 0 || H < 1 || W < 1 || C < 1 || k < 1 || stride < 1 || pad < 0 || pad >= k)
+        return NMO_ERR_ARG;
+    const int32_t Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < (int64_t)B * Ho * Wo; ++r) {
+        const int32_t wo = (int32_t)(r % Wo), ho = (int32_t)((r / Wo) % Ho), b = (int32_t)(r / ((int64_t)Wo * Ho));
+        for (int32_t c = 0; c < C; ++c) {
+            int32_t best = -128;
+            for (int32_t i = 0; i < k; ++i)
+                for (int32_t j = 0; j < k; ++j) {
+                    const int32_t hi = ho * stride - pad + i, wi = wo * stride - pad + j;
+                    if (hi < 0 || hi >= H || wi < 0 || wi >= W) continue;
+                    const int32_t v = x[(((size_t)b * H + hi) * W + wi) * C + c];
+                    if (v > best) best = v;
+                }
+            y[(size_t)r * C + c] = (int8_t)best;
+        }
+    }
+    return NMO_OK;
+}
+
+/*
+ * Global average pooling, a linear operation (Section 3.1: a product with a constant matrix):
+ * acc[b,c] = sum over the H*W positions of x[b,.,.,c] (exact in int32),
+ * v = (float)acc * alpha with alpha = (float)(s_x / (H*W)) supplied by the caller, requantised.
+ * x: int8 [B, HW, C] -> out_q int8 [B, C], out_f32 fp32 [B, C] (either may be NULL).
+ */
+int nmo_avgpool_i8(const int8_t* x, int32_t B, int32_t HW, int32_t C, float alpha,
+                   float out_inv_scale, int8_t* out_q, float* out_f32)
+{
+    if (!x || B < 0 || HW < 1 || C < 1) return NMO_ERR_ARG;
+    for (int32_t b = 0; b < B; ++b)
+        for (int32_t c = 0; c < C; ++c) {
+            int32_t acc = 0;
+            for (int32_t p = 0; p < HW; ++p) acc += x[((size_t)b * HW + p) * C + c];
+            const float v = (float)acc * alpha;
+            if (out_f32) out_f32[(size_t)b * C + c] = v;
+            if (out_q) out_q[(size_t)b * C + c] = requant(v, out_inv_scale);
+        }
+    return NMO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
 /* One post-LayerNorm transformer encoder layer (BERT ordering), no mask, no dropout.           */
 /* ------------------------------------------------------------------------------------------- */
 

@@ -38,6 +38,14 @@ class CGemm(C.Structure):
                 ("out_acc", C.c_void_p), ("dbg_seg", C.c_void_p)]
 
 
+class CConv(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "H", "W", "Cin", "Cout", "kh", "kw", "stride", "pad")] + [
+        ("x", C.c_void_p), ("w", C.c_void_p), ("bias", C.c_void_p), ("alpha_vec", C.c_void_p),
+        ("alpha", C.c_float), ("resid", C.c_void_p), ("resid_scale", C.c_float),
+        ("table", C.POINTER(CTable)), ("out_inv_scale", C.c_float), ("out_q", C.c_void_p),
+        ("out_f32", C.c_void_p), ("out_acc", C.c_void_p)]
+
+
 _LAYER_FLOATS = ["alpha_qkv", "inv_s_q", "inv_s_k", "inv_s_v", "alpha_scores", "inv_s_p",
                  "alpha_ctx", "inv_s_ctx", "alpha_o", "resid1_scale", "inv_s_ln1", "alpha_1",
                  "inv_s_ffn1", "alpha_2", "resid2_scale", "inv_s_out"]
@@ -108,6 +116,10 @@ def lib() -> C.CDLL:
                                             C.c_int64, C.c_int32, C.POINTER(CTable), C.c_float,
                                             C.c_void_p, C.c_void_p, C.c_void_p]
             L.nmo_gemm_pwl.argtypes = [C.POINTER(CGemm)]
+            L.nmo_conv2d_pwl.argtypes = [C.POINTER(CConv)]
+            L.nmo_maxpool_i8.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p]
+            L.nmo_avgpool_i8.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                         C.c_float, C.c_void_p, C.c_void_p]
             L.nmo_encoder_layer.argtypes = [C.POINTER(CLayer), C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.POINTER(CTaps)]
             L.nmo_encoder_layer_exact.argtypes = [C.POINTER(CLayer), C.c_void_p, C.c_int32,
@@ -287,6 +299,52 @@ def gemm_pwl(A, W, bias=None, alpha=1.0, alpha_vec=None, resid=None, resid_scale
               _p(acc), _p(seg))
     _check(lib().nmo_gemm_pwl(C.byref(g)), "gemm_pwl")
     return dict(acc=acc, y=y, q=q, seg=seg)
+
+
+def conv_out_hw(H, W, kh, kw, stride, pad):
+    return (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+
+
+def conv2d_pwl(x, w, stride=1, pad=0, bias=None, alpha=1.0, alpha_vec=None, resid=None,
+               resid_scale=0.0, table: Table | None = None, out_inv_scale=1.0, want_acc=True):
+    """x [B,H,W,Cin] int8, w [Cout,kh,kw,Cin] int8.  Returns dict(acc, y, q), each [B,Ho,Wo,Cout]."""
+    x = _arr(x, np.int8)
+    w = _arr(w, np.int8)
+    B, H, W, Cin = x.shape
+    Cout, kh, kw, _ = w.shape
+    assert w.shape[3] == Cin
+    Ho, Wo = conv_out_hw(H, W, kh, kw, stride, pad)
+    bias = _arr(bias, np.float32)
+    alpha_vec = _arr(alpha_vec, np.float32)
+    resid = _arr(resid, np.int8)
+    acc = np.empty((B, Ho, Wo, Cout), np.int32) if want_acc else None
+    y = np.empty((B, Ho, Wo, Cout), np.float32)
+    q = np.empty((B, Ho, Wo, Cout), np.int8)
+    g = CConv(B, H, W, Cin, Cout, kh, kw, stride, pad, _p(x), _p(w), _p(bias), _p(alpha_vec), alpha,
+              _p(resid), resid_scale, C.pointer(table.c) if table is not None else None,
+              out_inv_scale, _p(q), _p(y), _p(acc))
+    _check(lib().nmo_conv2d_pwl(C.byref(g)), "conv2d_pwl")
+    return dict(acc=acc, y=y, q=q)
+
+
+def maxpool_i8(x, k=3, stride=2, pad=1):
+    x = _arr(x, np.int8)
+    B, H, W, Cc = x.shape
+    Ho, Wo = conv_out_hw(H, W, k, k, stride, pad)
+    y = np.empty((B, Ho, Wo, Cc), np.int8)
+    _check(lib().nmo_maxpool_i8(_p(x), B, H, W, Cc, k, stride, pad, _p(y)), "maxpool_i8")
+    return y
+
+
+def avgpool_i8(x, alpha, out_inv_scale):
+    """x [B, HW, C] int8 -> dict(q [B,C] int8, y [B,C] fp32)."""
+    x = _arr(x, np.int8)
+    B, HW, Cc = x.shape
+    q = np.empty((B, Cc), np.int8)
+    y = np.empty((B, Cc), np.float32)
+    _check(lib().nmo_avgpool_i8(_p(x), B, HW, Cc, C.c_float(alpha), C.c_float(out_inv_scale), _p(q), _p(y)),
+           "avgpool_i8")
+    return dict(q=q, y=y)
 
 
 def _make_layer(p: dict, tables: dict):
