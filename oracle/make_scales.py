@@ -24,7 +24,9 @@ from paper_2305_14405_amd import workloads as W  # noqa: E402
 _FUNC = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
 # batch used for calibration: activations are i.i.d. over sequences, a few are enough
 CALIB_BATCH = {"bert_base_s512": 2, "bert_large_s512": 1}
-DEFAULT = ("tiny", "ragged", "bert_base_layer", "bert_base_s512", "bert_large_s512")
+DEFAULT = ("tiny", "ragged", "bert_base_layer", "bert_base_s512", "bert_large_s512",
+           "resnet_tiny", "resnet_odd", "resnet50")
+RESNET_CALIB_BATCH = {"resnet50": 2}
 
 
 def oracle_tables(cfg):
@@ -32,7 +34,16 @@ def oracle_tables(cfg):
             for n, (f, lo, hi, nseg) in W.table_ranges(cfg).items()}
 
 
+def calibrate_resnet(name: str, seed: int = 0) -> dict:
+    """The residual CNN: its only nonlinearity, ReLU, is exact as a PWL table, so the calibration
+    run is the oracle's own network with each tensor's scale taken from its fp32 values as it goes."""
+    t = W.resnet_tensors(name, seed, RESNET_CALIB_BATCH.get(name))
+    return O.resnet_forward(t, calibrate=True)["scales"]
+
+
 def calibrate(name: str, seed: int = 0) -> dict:
+    if name in W.RESNET_CONFIGS:
+        return calibrate_resnet(name, seed)
     cfg = W.config(name)
     t = W.layer_tensors(cfg, seed)
     if name in CALIB_BATCH:

@@ -347,6 +347,71 @@ def avgpool_i8(x, alpha, out_inv_scale):
     return dict(q=q, y=y)
 
 
+def relu_table() -> Table:
+    """max(x, 0) as a PWL table: two chord segments on a symmetric range are exact (k = {0, 1})."""
+    return build_table(F_RELU, -8.0, 8.0, 2)
+
+
+def resnet_forward(p: dict, x=None, calibrate: bool = False, keep: bool = False):
+    """The residual CNN of the workload generator, operation by operation (convolutions with the
+    folded batch-norm scale / bias, ReLU as a PWL table, exact int8 max pooling, linear average
+    pooling, classifier as a matrix product).  ``calibrate``: instead of using p's activation
+    scales, set each tensor's scale to absmax / 127 of its fp32 values as the network runs
+    (Section 3.2 step 1: ranges come from running the model) and return them.
+    Returns dict(logits fp32 [B, classes], tensors {name: int8} if keep, scales if calibrate)."""
+    relu = relu_table()
+    act = dict(x=p["s_x"]) if calibrate else p["act_scales"]
+    cur = {"x": _arr(p["x"] if x is None else x, np.int8)}
+    out = {}
+    for op in p["graph"]:
+        n = op["name"]
+        src = cur[op["src"]]
+        if op["op"] == "conv":
+            resid = cur[op["resid"]] if op["resid"] else None
+            if calibrate:
+                av = (act[op["src"]] * p["s_w"][n] * p["gain"][n]).astype(np.float32)
+                rs = float(np.float32(act[op["resid"]])) if op["resid"] else 0.0
+            else:
+                av, rs = p["alpha_vec"][n], p["resid_scale"][n]
+            kw = dict(stride=op["stride"], pad=op["pad"], bias=p["bias"][n], alpha_vec=av, resid=resid,
+                      resid_scale=rs, table=relu if op["relu"] else None, want_acc=False)
+            if calibrate:
+                y = conv2d_pwl(src, p["w"][n], out_inv_scale=1.0, **kw)["y"]
+                act[op["dst"]] = float(np.abs(y).max()) / 127.0
+                inv = float(np.float32(1.0 / act[op["dst"]]))
+            else:
+                inv = p["inv_s"][n]
+            cur[op["dst"]] = conv2d_pwl(src, p["w"][n], out_inv_scale=inv, **kw)["q"]
+        elif op["op"] == "maxpool":
+            cur[op["dst"]] = maxpool_i8(src, op["k"], op["stride"], op["pad"])
+            if calibrate:
+                act[op["dst"]] = act[op["src"]]
+        elif op["op"] == "avgpool":
+            B = src.shape[0]
+            flat = src.reshape(B, -1, op["C"])
+            if calibrate:
+                alpha = float(np.float32(act[op["src"]] / (op["H"] * op["H"])))
+                y = avgpool_i8(flat, alpha, 1.0)["y"]
+                act[op["dst"]] = float(np.abs(y).max()) / 127.0
+                inv = float(np.float32(1.0 / act[op["dst"]]))
+            else:
+                alpha, inv = p["alpha"][n], p["inv_s"][n]
+            cur[op["dst"]] = avgpool_i8(flat, alpha, inv)["q"]
+        elif op["op"] == "fc":
+            alpha = float(np.float32(act[op["src"]] * p["s_w"][n])) if calibrate else p["alpha"][n]
+            out["logits"] = gemm_pwl(src, p["w"][n], bias=p["bias"][n], alpha=alpha)["y"]
+        if not keep and op["op"] != "fc":  # drop tensors nothing reads any more
+            live = {o["src"] for o in p["graph"][p["graph"].index(op) + 1:]} | \
+                   {o.get("resid") for o in p["graph"][p["graph"].index(op) + 1:]}
+            for k in [k for k in cur if k not in live]:
+                del cur[k]
+    if keep:
+        out["tensors"] = cur
+    if calibrate:
+        out["scales"] = act
+    return out
+
+
 def _make_layer(p: dict, tables: dict):
     """p: the layer parameter dict produced by the workload generator (numpy arrays + floats).
     Returns (CLayer, keepalive list)."""

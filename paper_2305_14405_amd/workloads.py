@@ -212,3 +212,118 @@ def sweep_values(lo: float, hi: float, n: int, seed: int = 0) -> np.ndarray:
     specials = np.array([0.0, -0.0, lo, hi, 1e30, -1e30, np.nextafter(np.float32(hi), np.float32(0))],
                         dtype=np.float32)
     return np.concatenate([v, grid, specials]).astype(np.float32)
+
+
+# ---------------------------------------------------------------------------------------------
+# Residual CNN workload (BASELINE config 3: ResNet-50-shaped network as int8 convolutions in
+# their matrix form, batch normalisation folded into a per-channel scale and bias, ReLU as a
+# two-segment PWL table).  Stand-in for the paper's ResNet-50 / ImageNet experiments: random
+# weights, inputs U(0, 1).
+# ---------------------------------------------------------------------------------------------
+
+RESNET_CONFIGS = {
+    # the real layer shapes: 224 x 224 x 3 input, bottleneck stages (3, 4, 6, 3), 1000 classes
+    "resnet50": dict(B=64, HW=224, stages=(3, 4, 6, 3), widths=(64, 128, 256, 512), classes=1000),
+    # the same channel widths on 32 x 32 images, one block per stage (parity tests: every kernel
+    # path of the big network at sizes the oracle finishes in a second)
+    "resnet_tiny": dict(B=2, HW=32, stages=(1, 1, 1, 1), widths=(64, 128, 256, 512), classes=10),
+    # channel counts that are multiples of nothing convenient (fallback paths)
+    "resnet_odd": dict(B=3, HW=20, stages=(1, 2), widths=(12, 20), classes=7),
+}
+RELU_TABLE = ("relu", -8.0, 8.0, 2)  # chords of max(x, 0) on a symmetric range: k = {0, 1}, b = {0, 0}
+
+
+def resnet_graph(cfg: dict) -> list:
+    """The network as a list of operations over named NHWC tensors (shapes only)."""
+    ops = []
+    hw = cfg["HW"]
+    w0 = cfg["widths"][0]
+
+    def conv(name, src, dst, cin, cout, k, stride, pad, h, relu, resid=None):
+        ho = (h + 2 * pad - k) // stride + 1
+        ops.append(dict(op="conv", name=name, src=src, dst=dst, Cin=cin, Cout=cout, k=k, stride=stride,
+                        pad=pad, H=h, Ho=ho, relu=relu, resid=resid))
+        return ho
+
+    h = conv("conv1", "x", "c1", 3, w0, 7, 2, 3, hw, True)
+    ho = (h + 2 - 3) // 2 + 1
+    ops.append(dict(op="maxpool", name="pool1", src="c1", dst="p1", C=w0, k=3, stride=2, pad=1, H=h, Ho=ho))
+    h, cur, cin = ho, "p1", w0
+    for si, (nblocks, mid) in enumerate(zip(cfg["stages"], cfg["widths"])):
+        for bi in range(nblocks):
+            stride = 2 if (bi == 0 and si > 0) else 1
+            pre = f"s{si}b{bi}"
+            cout = 4 * mid
+            conv(pre + "a", cur, pre + "a", cin, mid, 1, 1, 0, h, True)
+            h2 = conv(pre + "b", pre + "a", pre + "b", mid, mid, 3, stride, 1, h, True)
+            short = cur
+            if bi == 0:  # projection shortcut (channel count and / or resolution change)
+                conv(pre + "d", cur, pre + "d", cin, cout, 1, stride, 0, h, False)
+                short = pre + "d"
+            conv(pre + "c", pre + "b", pre + "c", mid, cout, 1, 1, 0, h2, True, resid=short)
+            h, cur, cin = h2, pre + "c", cout
+    ops.append(dict(op="avgpool", name="avgpool", src=cur, dst="gap", C=cin, H=h))
+    ops.append(dict(op="fc", name="fc", src="gap", dst="logits", Cin=cin, Cout=cfg["classes"]))
+    return ops
+
+
+def resnet_tensors(name: str, seed: int = 0, batch: int | None = None) -> dict:
+    """Weights (one PCG64 stream, drawn in graph order: weight, folded-BN gain, bias per
+    convolution; then the classifier) and the input image batch (its own stream, so that the
+    weights do not depend on the batch size).  Weights ~ N(0, 2 / fan_in) quantised per tensor;
+    folded batch-norm gain ~ 1 + N(0, 0.1^2) (0.25 + ... on the last convolution of a block and
+    on projection shortcuts, which keeps the residual sums O(1)), bias ~ N(0, 0.1^2);
+    images ~ U(0, 1) with scale 1/127."""
+    cfg = dict(RESNET_CONFIGS[name])
+    B = batch if batch is not None else cfg["B"]
+    g = np.random.Generator(np.random.PCG64(seed))
+    t = dict(cfg=cfg, B=B, graph=resnet_graph(cfg), w={}, s_w={}, gain={}, bias={})
+    for op in t["graph"]:
+        if op["op"] == "conv":
+            k, cin, cout = op["k"], op["Cin"], op["Cout"]
+            std = np.sqrt(2.0 / (k * k * cin))
+            wt = (std * g.standard_normal((cout, k, k, cin), dtype=np.float32)).astype(np.float32)
+            t["w"][op["name"]], t["s_w"][op["name"]] = quantize_sym(wt)
+            base = 1.0 if op["relu"] and op["resid"] is None else 0.25
+            t["gain"][op["name"]] = (base * (1.0 + 0.1 * g.standard_normal(cout))).astype(np.float64)
+            t["bias"][op["name"]] = (0.1 * g.standard_normal(cout)).astype(np.float32)
+        elif op["op"] == "fc":
+            wt = (np.sqrt(1.0 / op["Cin"]) * g.standard_normal((op["Cout"], op["Cin"]), dtype=np.float32))
+            t["w"]["fc"], t["s_w"]["fc"] = quantize_sym(wt.astype(np.float32))
+            t["bias"]["fc"] = (0.1 * g.standard_normal(op["Cout"])).astype(np.float32)
+    gi = np.random.Generator(np.random.PCG64(seed + 1000))
+    img = gi.random((B, cfg["HW"], cfg["HW"], 3), dtype=np.float32)
+    t["x"] = np.clip(np.rint(img.astype(np.float64) * 127.0), -127, 127).astype(np.int8)
+    t["s_x"] = 1.0 / 127.0
+    return t
+
+
+def resnet_with_scales(t: dict, act: dict) -> dict:
+    """Adds, per operation, the fp32 numbers both implementations receive (formed in binary64,
+    rounded once): per-channel dequantisation scale alpha_vec = s_in * s_w * gain, residual scale,
+    inverse output scale.  ``act`` maps tensor name -> scale (the input 'x' included)."""
+    p = dict(t)
+    p["alpha_vec"], p["resid_scale"], p["inv_s"], p["alpha"] = {}, {}, {}, {}
+    f32 = lambda v: float(np.float32(v))  # noqa: E731
+    for op in t["graph"]:
+        n = op["name"]
+        if op["op"] == "conv":
+            p["alpha_vec"][n] = (act[op["src"]] * t["s_w"][n] * t["gain"][n]).astype(np.float32)
+            p["resid_scale"][n] = f32(act[op["resid"]]) if op["resid"] else 0.0
+            p["inv_s"][n] = f32(1.0 / act[op["dst"]])
+        elif op["op"] == "avgpool":
+            p["alpha"][n] = f32(act[op["src"]] / (op["H"] * op["H"]))
+            p["inv_s"][n] = f32(1.0 / act[op["dst"]])
+        elif op["op"] == "fc":
+            p["alpha"][n] = f32(act[op["src"]] * t["s_w"][n])
+    p["act_scales"] = dict(act)
+    return p
+
+
+def resnet_params(name: str, seed: int = 0, batch: int | None = None) -> dict:
+    with open(SCALES_JSON) as f:
+        table = json.load(f)
+    key = f"{name}/seed{seed}"
+    if key not in table:
+        raise KeyError(f"no stored activation scales for {key}; run oracle/make_scales.py")
+    return resnet_with_scales(resnet_tensors(name, seed, batch), table[key])

@@ -126,3 +126,37 @@ def test_avgpool_is_the_scaled_integer_sum(oracle):
     assert np.array_equal(r["q"], wq)
     const = np.full((1, 16, 4), 64, np.int8)  # a constant image averages to itself: 16 * 64 / 16
     assert np.all(oracle.avgpool_i8(const, 1.0 / 16, 1.0)["y"] == 64.0)
+
+
+@pytest.mark.parametrize("name", ["resnet_odd", "resnet_tiny"])
+def test_resnet_forward_tracks_a_float64_library_network(oracle, name):
+    """The oracle's int8 residual network against the same network in float64 with library
+    operators and no activation rounding (weights dequantised, batch-norm gain and bias applied
+    per channel, ReLU, residual sums, pooling, classifier): the wiring (strides, shortcuts,
+    which tensor feeds which) must agree, so the logits differ only by quantisation noise."""
+    from paper_2305_14405_amd import workloads as W
+    p = W.resnet_params(name, 0)
+    got = oracle.resnet_forward(p)["logits"]
+    F = torch.nn.functional
+    cur = {"x": torch.from_numpy(p["x"].astype(np.float64) * p["s_x"]).permute(0, 3, 1, 2)}
+    for op in p["graph"]:
+        n = op["name"]
+        if op["op"] == "conv":
+            w = torch.from_numpy(p["w"][n].astype(np.float64) * p["s_w"][n]).permute(0, 3, 1, 2)
+            y = F.conv2d(cur[op["src"]], w, stride=op["stride"], padding=op["pad"])
+            y = y * torch.from_numpy(p["gain"][n]).view(1, -1, 1, 1) + \
+                torch.from_numpy(p["bias"][n].astype(np.float64)).view(1, -1, 1, 1)
+            if op["resid"]:
+                y = y + cur[op["resid"]]
+            cur[op["dst"]] = torch.relu(y) if op["relu"] else y
+        elif op["op"] == "maxpool":
+            cur[op["dst"]] = F.max_pool2d(cur[op["src"]], op["k"], op["stride"], op["pad"])
+        elif op["op"] == "avgpool":
+            cur[op["dst"]] = cur[op["src"]].mean(dim=(2, 3))
+        elif op["op"] == "fc":
+            w = torch.from_numpy(p["w"][n].astype(np.float64) * p["s_w"][n])
+            want = (cur[op["src"]] @ w.T + torch.from_numpy(p["bias"][n].astype(np.float64))).numpy()
+    assert got.shape == want.shape
+    rel = np.sqrt(((got - want) ** 2).mean() / (want ** 2).mean())
+    assert rel < 0.05, rel
+    assert np.abs(want).max() > 0.05  # the logits are not degenerate
