@@ -320,6 +320,61 @@ int32_t nm_encoder_stack_workspace(const nm_layer_desc* descs, int32_t n_layers,
 int32_t nm_encoder_stack(const nm_layer_desc* descs, int32_t n_layers, const int8_t* x, int8_t* y_q,
                          float* y_f32, void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * nm_conv2d_pwl: int8 convolution in its matrix form (paper Section 3.1: a convolution becomes a
+ * matrix product whose dimensions follow from the width, height and channel counts) with the
+ * epilogue of nm_gemm_pwl:
+ *   acc[b,ho,wo,n] = sum_{i,j,c} x[b, ho*stride - pad + i, wo*stride - pad + j, c] * w[n,i,j,c]
+ *                    (exact int32; positions outside the image contribute nothing)
+ *   v = fma((float)acc, alpha_n, bias_n);  v = fma((float)resid, resid_scale, v) if resid;
+ *   v = PWL(v) if table_idx >= 0 (ReLU is the exact two-segment table);  outputs v and its int8 code.
+ * Ho = (H + 2*pad - kh) / stride + 1, Wo likewise.
+ * x: device int8 [B, H, W, Cin] (channels contiguous).  w: device int8 [Cout, kh, kw, Cin].
+ * bias, alpha_vec: device fp32 [Cout] or NULL (alpha_vec NULL -> alpha; a folded batch
+ * normalisation is a per-channel alpha_vec and bias).  resid: device int8 [B, Ho, Wo, Cout] or
+ * NULL.  Outputs (device, any may be NULL, at least one required): out_q int8, out_f32, dbg_acc
+ * int32, each [B, Ho, Wo, Cout].
+ * Workspace: needed only when Cin is not a multiple of 64 (or x / w are not 16-byte aligned) and
+ * the convolution is not 1x1 / stride 1 / no padding; query nm_conv2d_workspace (0 otherwise; ws
+ * may then be NULL).  256-byte aligned, contents are scratch.  Nothing is allocated, the host
+ * does not wait.  Limits: kh*kw*Cin <= 65536, B*Ho*Wo < 2^31, B*Ho*Wo*Cout < 2^31.
+ * --------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t B, H, W, Cin, Cout, kh, kw, stride, pad;
+    const int8_t* x;
+    const int8_t* w;
+    const float* bias;
+    const float* alpha_vec;
+    float alpha;
+    const int8_t* resid;
+    float resid_scale;
+    const nm_tables* tables;
+    int32_t table_idx; /* -1: no table */
+    float out_inv_scale;
+    int8_t* out_q;
+    float* out_f32;
+    int32_t* dbg_acc;
+} nm_conv_desc;
+
+int32_t nm_conv2d_workspace(const nm_conv_desc* desc, size_t* bytes);
+int32_t nm_conv2d_pwl(const nm_conv_desc* desc, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * nm_maxpool_i8: k x k max pooling on int8 codes that share one scale (exact; the paper does not
+ * discuss pooling).  Positions outside the image never take part.  x: device int8 [B, H, W, C];
+ * y: device int8 [B, Ho, Wo, C] with Ho = (H + 2*pad - k) / stride + 1.  Requires pad < k.
+ */
+int32_t nm_maxpool_i8(const int8_t* x, int32_t B, int32_t H, int32_t W, int32_t C, int32_t k,
+                      int32_t stride, int32_t pad, int8_t* y, void* stream);
+
+/*
+ * nm_avgpool_i8: global average pooling as the linear operation it is (Section 3.1):
+ * acc[b,c] = sum over the HW positions (exact int32), v = (float)acc * alpha with alpha =
+ * s_x / HW formed by the caller, out_f32 = v, out_q = its int8 code.  x: device int8 [B, HW, C].
+ */
+int32_t nm_avgpool_i8(const int8_t* x, int32_t B, int32_t HW, int32_t C, float alpha, float out_inv_scale,
+                      int8_t* out_q, float* out_f32, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,8 @@ EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_table
            "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_destroy",
            "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_pwl_apply", "nm_attn_scores",
            "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer",
-           "nm_encoder_stack_workspace", "nm_encoder_stack")
+           "nm_encoder_stack_workspace", "nm_encoder_stack", "nm_conv2d_workspace", "nm_conv2d_pwl",
+           "nm_maxpool_i8", "nm_avgpool_i8")
 
 
 class NmError(RuntimeError):
@@ -44,6 +45,14 @@ class GemmDesc(C.Structure):
                 ("tables", C.c_void_p), ("table_idx", C.c_int32), ("out_inv_scale", C.c_float),
                 ("out_inv_scale_vec", C.c_void_p), ("out_q", C.c_void_p), ("out_f32", C.c_void_p),
                 ("out_acc", C.c_void_p), ("dbg_seg", C.c_void_p)]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "H", "W", "Cin", "Cout", "kh", "kw", "stride", "pad")] + [
+        ("x", C.c_void_p), ("w", C.c_void_p), ("bias", C.c_void_p), ("alpha_vec", C.c_void_p),
+        ("alpha", C.c_float), ("resid", C.c_void_p), ("resid_scale", C.c_float),
+        ("tables", C.c_void_p), ("table_idx", C.c_int32), ("out_inv_scale", C.c_float),
+        ("out_q", C.c_void_p), ("out_f32", C.c_void_p), ("dbg_acc", C.c_void_p)]
 
 
 LAYER_FLOATS = ("alpha_qkv", "inv_s_q", "inv_s_k", "inv_s_v", "alpha_scores", "inv_s_p",
@@ -117,6 +126,11 @@ def load(preload_torch: bool = True) -> C.CDLL:
     L.nm_encoder_layer_workspace.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_size_t)]
     L.nm_encoder_layer.argtypes = [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.POINTER(LayerTaps), C.c_void_p]
+    L.nm_conv2d_workspace.argtypes = [C.POINTER(ConvDesc), C.POINTER(C.c_size_t)]
+    L.nm_conv2d_pwl.argtypes = [C.POINTER(ConvDesc), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.nm_maxpool_i8.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
+    L.nm_avgpool_i8.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_float,
+                                C.c_void_p, C.c_void_p, C.c_void_p]
     L.nm_encoder_stack_workspace.argtypes = [C.POINTER(LayerDesc), C.c_int32, C.POINTER(C.c_size_t)]
     L.nm_encoder_stack.argtypes = [C.POINTER(LayerDesc), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]
@@ -341,3 +355,44 @@ def nm_encoder_stack(descs, x, y_q, y_f32, ws, stream=None, ws_bytes=None):
     nbytes = ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes
     _check(load().nm_encoder_stack(_desc_array(descs), len(descs), _ptr(x), _ptr(y_q), _ptr(y_f32),
                                    _ptr(ws), nbytes, _stream(stream)))
+
+
+def make_conv_desc(x, w, stride=1, pad=0, *, bias=None, alpha=1.0, alpha_vec=None, resid=None,
+                   resid_scale=0.0, tables: Tables | None = None, table_idx=-1, out_inv_scale=1.0,
+                   out_q=None, out_f32=None, dbg_acc=None) -> ConvDesc:
+    """x [B,H,W,Cin] int8 device tensor, w [Cout,kh,kw,Cin] int8 device tensor."""
+    d = ConvDesc()
+    d.B, d.H, d.W, d.Cin = (int(v) for v in x.shape)
+    d.Cout, d.kh, d.kw = int(w.shape[0]), int(w.shape[1]), int(w.shape[2])
+    d.stride, d.pad = stride, pad
+    d.x, d.w, d.bias, d.alpha_vec = _ptr(x), _ptr(w), _ptr(bias), _ptr(alpha_vec)
+    d.alpha = alpha
+    d.resid, d.resid_scale = _ptr(resid), resid_scale
+    d.tables = tables.handle if tables is not None else None
+    d.table_idx = table_idx
+    d.out_inv_scale = out_inv_scale
+    d.out_q, d.out_f32, d.dbg_acc = _ptr(out_q), _ptr(out_f32), _ptr(dbg_acc)
+    return d
+
+
+def nm_conv2d_workspace(desc: ConvDesc) -> int:
+    n = C.c_size_t()
+    _check(load().nm_conv2d_workspace(C.byref(desc), C.byref(n)))
+    return n.value
+
+
+def nm_conv2d_pwl(desc: ConvDesc, ws=None, stream=None, ws_bytes=None):
+    nbytes = 0 if ws is None else (ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes)
+    _check(load().nm_conv2d_pwl(C.byref(desc), _ptr(ws), nbytes, _stream(stream)))
+
+
+def nm_maxpool_i8(x, y, k=3, stride=2, pad=1, stream=None):
+    B, H, W, Cc = (int(v) for v in x.shape)
+    _check(load().nm_maxpool_i8(_ptr(x), B, H, W, Cc, k, stride, pad, _ptr(y), _stream(stream)))
+
+
+def nm_avgpool_i8(x, alpha, out_inv_scale, *, out_q=None, out_f32=None, stream=None):
+    """x [B, HW, C] int8 device tensor."""
+    B, HW, Cc = (int(v) for v in x.shape)
+    _check(load().nm_avgpool_i8(_ptr(x), B, HW, Cc, alpha, out_inv_scale, _ptr(out_q), _ptr(out_f32),
+                                _stream(stream)))

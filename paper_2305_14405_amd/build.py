@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libnm_hip.so")
-SOURCES = ["nm_tables.cpp", "nm_rows.hip", "nm_gemm.hip", "nm_attention.hip", "nm_layer.cpp"]
+SOURCES = ["nm_tables.cpp", "nm_rows.hip", "nm_gemm.hip", "nm_attention.hip", "nm_conv.hip", "nm_layer.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -55,7 +55,14 @@ struct GemmParams {
     int32_t* out_acc;
     uint16_t* dbg_seg;
     int tiles_m, tiles_n;
+    // convolution in matrix form (streaming kernel with kConv): row m of A is the output position
+    // (b, ho, wo), column k the (tap, channel) pair; A points to the NHWC image tensor
+    int cH, cW, cCin, cKw, cStride, cPad, cHo, cWo;
 };
+
+// A line of zeros in device memory: the source of operand bytes that fall into a convolution's
+// padding (the direct global -> LDS loads cannot substitute a value, only an address).
+__device__ __attribute__((aligned(256))) int8_t g_zero_line[256];
 
 // XOR swizzle of the 16-byte chunk index inside a 64-byte LDS row: rows that fall into the same
 // bank window get different chunk positions, for both a 128-byte and a 256-byte wide LDS port.
@@ -141,7 +148,7 @@ __device__ __forceinline__ void load_cols(const GemmParams& p, int nb, Col4& c)
     for (int e = 0; e < 4; ++e) { c.scale[e] = alpha; c.bias[e] = 0.0f; c.inv[e] = ois; }
     if (kEpi == EPI_ACC) return;
     if (p.bias) load4(p.bias, nb, p.N, p.vec_cols, c.bias);
-    if (kEpi == EPI_GENERIC && p.alpha_vec) load4(p.alpha_vec, nb, p.N, p.vec_cols, c.scale);
+    if (p.alpha_vec) load4(p.alpha_vec, nb, p.N, p.vec_cols, c.scale);
     if (kEpi == EPI_F32_RESID) return;
     if (kEpi == EPI_GENERIC && p.out_inv_scale_vec) {
         load4(p.out_inv_scale_vec, nb, p.N, p.vec_cols, c.inv);
@@ -402,7 +409,13 @@ __device__ __forceinline__ int lds_off_bk(int row, int chunk)
 // halves of their int32 partial accumulators through LDS (integer addition is exact in any
 // order) and each finishes half of the sub-tile's rows, which also halves the epilogue per
 // wavefront.  Used where the grid has fewer workgroups than CUs times two (N = 768 GEMMs).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages, int kEpi>
+//
+// kConv: the A operand is gathered from an NHWC image (convolution as a matrix product, paper
+// Section 3.1).  A k-slice never straddles a filter tap (Cin % BK == 0), so for the slice of tap
+// (i, j) and channels c0.. a lane's 16 bytes are x[b, ho*stride - pad + i, wo*stride - pad + j,
+// c0 + 16*chunk ..] or, in the padding, 16 bytes of the zero line; only the per-lane source
+// address of the direct global -> LDS load changes, the rest of the kernel is the same.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages, int kEpi, bool kConv = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_kernel(GemmParams p)
 {
     constexpr int NWT = WAVES_M * WAVES_N;       // wavefront tiles per workgroup
@@ -467,7 +480,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_k
             float sc = p.alpha, bi = 0.0f, iv = p.out_inv_scale;
             if (n < p.N) {
                 if (p.bias) bi = p.bias[n];
-                if (kEpi == EPI_GENERIC && p.alpha_vec) sc = p.alpha_vec[n];
+                if (p.alpha_vec) sc = p.alpha_vec[n];
                 if (kEpi == EPI_GENERIC && p.out_inv_scale_vec) iv = p.out_inv_scale_vec[n];
                 else if (p.split_cols > 0) iv = n >= 2 * p.split_cols ? p.inv3[2] : (n >= p.split_cols ? p.inv3[1] : p.inv3[0]);
             }
@@ -479,6 +492,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_k
 
     // per-lane source pointers of this wavefront's blocks (k = 0)
     const int8_t* src[LB];
+    int conv_h[LB], conv_w[LB];  // kConv, A rows: top-left input coordinate of the lane's output position
     const bool has_last = wave + (LB - 1) * NW < NBLK;  // wave-uniform
 #pragma unroll
     for (int b = 0; b < LB; ++b) {
@@ -486,18 +500,49 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_k
         if (blk >= NBLK) blk = wave;  // unused slot
         const int r = blk * RPI + lane / CPR;
         const int chunk = (lane % CPR) ^ swz_bk<BK>(r);
-        if (r < BM) src[b] = A + (long)min(m0 + r, p.M - 1) * p.lda + 16 * chunk;
-        else src[b] = W + (long)min(n0 + r - BM, p.N - 1) * p.ldw + 16 * chunk;
+        conv_h[b] = 0; conv_w[b] = 0;
+        if (r < BM) {
+            const int m = min(m0 + r, p.M - 1);
+            if (kConv) {
+                const int wo = m % p.cWo, t = m / p.cWo;
+                const int ho = t % p.cHo, bi = t / p.cHo;
+                conv_h[b] = ho * p.cStride - p.cPad;
+                conv_w[b] = wo * p.cStride - p.cPad;
+                src[b] = A + (long)bi * p.cH * p.cW * p.cCin + 16 * chunk;  // image base + chunk
+            } else {
+                src[b] = A + (long)m * p.lda + 16 * chunk;
+            }
+        } else {
+            src[b] = W + (long)min(n0 + r - BM, p.N - 1) * p.ldw + 16 * chunk;
+        }
     }
     const unsigned lds_base = (unsigned)(uintptr_t)smem;
     // Issue the loads of k-slice kt into ring slot `stage`; with parts > 1 only the blocks b with
     // b % parts == part, so that the issue slots can be spread between the MFMAs of the main loop
     // (a wavefront issues in order: a burst of LB loads would stall its MFMA stream).
+    // kConv: slices are issued in increasing kt, so the tap (ti, tj) and the channel offset tc of
+    // the slice being issued are kept as running (wave-uniform) counters.
+    int ti = 0, tj = 0, tc = 0;
     auto issue = [&](int kt, int stage, int part, int parts) {
         const unsigned dst = lds_base + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
         for (int b = 0; b < LB; ++b)
-            if (b % parts == part && (b < LB - 1 || has_last)) dma16(src[b] + (long)kt * BK, dst + b * NW * 1024);
+            if (b % parts == part && (b < LB - 1 || has_last)) {
+                const int blk = wave + b * NW;
+                if (kConv && blk * RPI < BM) {  // wave-uniform: an A block
+                    const int hi = conv_h[b] + ti, wi = conv_w[b] + tj;
+                    const bool inside = (unsigned)hi < (unsigned)p.cH && (unsigned)wi < (unsigned)p.cW;
+                    const int8_t* g = inside ? src[b] + ((long)hi * p.cW + wi) * p.cCin + tc
+                                             : g_zero_line + 16 * (lane % CPR);
+                    dma16(g, dst + b * NW * 1024);
+                } else {
+                    dma16(src[b] + (long)kt * BK, dst + b * NW * 1024);
+                }
+            }
+        if (kConv && part == parts - 1) {  // the slice is complete: advance to the next one
+            tc += BK;
+            if (tc == p.cCin) { tc = 0; if (++tj == p.cKw) { tj = 0; ++ti; } }
+        }
     };
 
     v16i acc[TM][TN];
@@ -691,10 +736,10 @@ static void launch_cfg(const GemmParams& p, bool al, bool wkn, dim3 grid, size_t
     else hipLaunchKernelGGL((gemm_pwl_kernel<BM, BN, WM, WN, false, true>), grid, dim3(kGemmThreads), shmem, s, p);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages, int kEpi>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages, int kEpi, bool kConv = false>
 static int32_t launch_stream_epi(GemmParams& p, int batches, size_t table_bytes, hipStream_t s)
 {
-    auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, kEpi>;
+    auto kern = gemm_stream_kernel<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, kEpi, kConv>;
     const size_t shmem = (size_t)kStages * (BM + BN) * BK + 3 * BN * sizeof(float) + table_bytes;
     static bool configured = false;  // one attribute call per instantiation
     if (!configured) {
@@ -722,6 +767,17 @@ static int32_t launch_stream(GemmParams& p, int epi, int batches, size_t table_b
     }
 }
 
+// Convolutions use three epilogues (everything else falls to the generic one).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages>
+static int32_t launch_stream_conv(GemmParams& p, int epi, size_t table_bytes, hipStream_t s)
+{
+    switch (epi) {
+    case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q, true>(p, 1, table_bytes, s);
+    case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q_TABLE, true>(p, 1, table_bytes, s);
+    default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_GENERIC, true>(p, 1, table_bytes, s);
+    }
+}
+
 int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
 {
     if (g.M == 0) return NM_OK;
@@ -738,6 +794,8 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     p.split_cols = g.split_cols;
     for (int i = 0; i < 3; ++i) p.inv3[i] = g.inv3[i];
     p.ldo = g.ldo;
+    p.cH = g.cH; p.cW = g.cW; p.cCin = g.cCin; p.cKw = g.cKw; p.cStride = g.cStride; p.cPad = g.cPad;
+    p.cHo = g.cHo; p.cWo = g.cWo;
     p.out_q = g.out_q; p.out_f32 = g.out_f32; p.out_acc = g.out_acc; p.dbg_seg = g.dbg_seg;
 
     // 16-byte loads need every row start and every batch offset on a 16-byte boundary
@@ -757,12 +815,23 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     p.vec_cols = (!g.bias || aligned(g.bias, 16)) && (!g.alpha_vec || aligned(g.alpha_vec, 16)) &&
                  (!g.out_inv_scale_vec || aligned(g.out_inv_scale_vec, 16));
     int epi = EPI_GENERIC;
-    if (!g.alpha_vec && !g.out_inv_scale_vec && !g.dbg_seg) {
+    if (!g.out_inv_scale_vec && !g.dbg_seg) {
         const bool only_q = g.out_q && !g.out_f32 && !g.out_acc;
         // EPI_Q_TABLE is compiled without the input clamp; a table with that flag takes the generic epilogue
         if (only_q && !g.resid) epi = !g.has_table ? EPI_Q : g.table.clamp_input ? EPI_GENERIC : EPI_Q_TABLE;
         else if (g.out_f32 && !g.out_q && !g.out_acc && g.resid && !g.has_table && p.vec_out) epi = EPI_F32_RESID;
         else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
+    }
+    if (g.conv) {
+        // gathered A operand: streaming kernel only (the caller has checked Cin % 64 == 0, 16-byte
+        // aligned image and weights); one problem, no batching
+        if (!w_al || !aligned(g.A, 16) || g.cCin % 64 != 0 || g.K != g.cCin * g.cKw * (g.K / (g.cCin * g.cKw)))
+            return fail(NM_ERR_UNSUPPORTED, "conv gemm: operands not aligned for the gathered loader");
+        if (g.N <= 64) rc = launch_stream_conv<256, 64, 4, 1, 1, 64, 4>(p, epi, table_bytes, stream);
+        else if (g.cCin % 128 == 0 && table_bytes <= 32768) rc = launch_stream_conv<128, 128, 2, 2, 2, 128, 3>(p, epi, table_bytes, stream);
+        else rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 3>(p, epi, table_bytes, stream);
+        if (rc) return rc;
+        return check_hip(hipGetLastError(), "conv gemm launch");
     }
     const bool stream_ok = al && !g.w_is_kn && g.K % 64 == 0 && !force_generic();
     const bool k128 = g.K % 128 == 0;  // 128-byte k-slices (whole L2 lines) fetch ~1.5x faster than 64-byte ones
@@ -773,6 +842,9 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         rc = launch_stream<128, 128, 2, 2, 2, 128, 3>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && g.N > 64) {
         rc = launch_stream<128, 128, 2, 2, 1, 64, 3>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && g.N > 32 && g.M >= 1024) {
+        // narrow outputs with many rows (the 64-channel convolutions of a residual CNN)
+        rc = launch_stream<256, 64, 4, 1, 1, 64, 4>(p, epi, batches, table_bytes, stream);
     } else if (g.N <= 64) {
         p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 63) / 64;
         launch_cfg<128, 64, 32, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), table_bytes, stream);

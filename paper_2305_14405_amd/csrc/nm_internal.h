@@ -72,6 +72,10 @@ struct GemmArgs {
     float* out_f32 = nullptr;
     int32_t* out_acc = nullptr;
     uint16_t* dbg_seg = nullptr;
+    // conv != 0: A is an NHWC image [B, cH, cW, cCin] and row m = (b, ho, wo) of the matrix is
+    // gathered from it (K = kh * cKw * cCin, tap major); M = B * cHo * cWo
+    int conv = 0;
+    int cH = 0, cW = 0, cCin = 0, cKw = 0, cStride = 1, cPad = 0, cHo = 0, cWo = 0;
 };
 
 int32_t launch_gemm(const GemmArgs& g, hipStream_t stream);
