@@ -76,6 +76,8 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.workload.startswith("resnet"):
+        return bench_resnet(args)
 
     import numpy as np
     import torch
@@ -310,6 +312,154 @@ def main():
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
                summary=summary,
                parity=parity)
+    print(json.dumps(out))
+
+
+def graph_timed(torch, fn, reps):
+    """Average duration (ms) of one call of fn: recorded reps times into a HIP graph, the replay
+    bracketed by events on the launch stream."""
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(reps):
+                fn()
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    graph.replay()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def bench_resnet(args):
+    """BASELINE config 3: the ResNet-50-shaped int8 network (convolutions in matrix form, folded
+    batch norm, ReLU as a two-segment PWL table), one C-ABI call per operation.  value = images/s."""
+    import numpy as np
+    import torch
+
+    from paper_2305_14405_amd import binding as nm
+    from paper_2305_14405_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    p = W.resnet_params(args.workload, 0)
+    B = p["B"]
+    tables = nm.nm_build_tables([W.RELU_TABLE])
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)  # noqa: E731
+    cur = {"x": t(p["x"])}
+    calls, keep, convs = [], [], []
+    ws_need = 256
+    for op in p["graph"]:
+        n = op["name"]
+        if op["op"] == "conv":
+            y = torch.empty((B, op["Ho"], op["Ho"], op["Cout"]), dtype=torch.int8, device=dev)
+            wt, bi, av = t(p["w"][n]), t(p["bias"][n]), t(p["alpha_vec"][n])
+            keep += [wt, bi, av]
+            d = nm.make_conv_desc(cur[op["src"]], wt, op["stride"], op["pad"], bias=bi, alpha_vec=av,
+                                  resid=cur[op["resid"]] if op["resid"] else None,
+                                  resid_scale=p["resid_scale"][n], tables=tables,
+                                  table_idx=0 if op["relu"] else -1, out_inv_scale=p["inv_s"][n], out_q=y)
+            ws_need = max(ws_need, nm.nm_conv2d_workspace(d))
+            convs.append((op, d))
+            calls.append(("conv", n, d))
+            cur[op["dst"]] = y
+        elif op["op"] == "maxpool":
+            y = torch.empty((B, op["Ho"], op["Ho"], op["C"]), dtype=torch.int8, device=dev)
+            calls.append(("maxpool", n, (cur[op["src"]], y, op["k"], op["stride"], op["pad"])))
+            cur[op["dst"]] = y
+        elif op["op"] == "avgpool":
+            y = torch.empty((B, op["C"]), dtype=torch.int8, device=dev)
+            calls.append(("avgpool", n, (cur[op["src"]].view(B, -1, op["C"]), p["alpha"][n], p["inv_s"][n], y)))
+            cur[op["dst"]] = y
+        elif op["op"] == "fc":
+            logits = torch.empty((B, op["Cout"]), dtype=torch.float32, device=dev)
+            wt, bi = t(p["w"][n]), t(p["bias"][n])
+            keep += [wt, bi]
+            calls.append(("fc", n, (cur[op["src"]], wt, bi, p["alpha"][n], logits)))
+    ws = torch.empty(ws_need, dtype=torch.uint8, device=dev)
+
+    def run(call):
+        kind, _, a = call
+        if kind == "conv":
+            nm.nm_conv2d_pwl(a, ws)
+        elif kind == "maxpool":
+            nm.nm_maxpool_i8(a[0], a[1], a[2], a[3], a[4])
+        elif kind == "avgpool":
+            nm.nm_avgpool_i8(a[0], a[1], a[2], out_q=a[3])
+        else:
+            nm.nm_gemm_pwl(a[0], a[1], bias=a[2], alpha=a[3], out_f32=a[4])
+
+    def step():
+        for c in calls:
+            run(c)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    kernels = []
+    for c in calls:
+        ms = graph_timed(torch, lambda c=c: run(c), max(2, args.kernel_reps // 5))
+        entry = dict(kernel=c[1], kind=c[0], ms=round(ms, 5))
+        if c[0] == "conv":
+            op = next(o for o, d in convs if o["name"] == c[1])
+            ops = 2.0 * B * op["Ho"] ** 2 * op["Cout"] * op["k"] ** 2 * op["Cin"]
+            ach = ops / (ms * 1e-3) / 1e12
+            entry.update(bound="mfma", achieved=round(ach, 1), peak=PEAK_INT8_TOPS, unit="TFLOP/s",
+                         frac=round(ach / PEAK_INT8_TOPS, 4),
+                         shape=f"M={B * op['Ho'] ** 2} N={op['Cout']} K={op['k'] ** 2 * op['Cin']} "
+                               f"k{op['k']} s{op['stride']}")
+        kernels.append(entry)
+    conv_k = [k for k in kernels if k["kind"] == "conv"]
+    dom = max(conv_k, key=lambda k: k["ms"])
+    total_ops = sum(2.0 * B * o["Ho"] ** 2 * o["Cout"] * o["k"] ** 2 * o["Cin"] for o, _ in convs)
+    conv_ms = sum(k["ms"] for k in conv_k)
+    roofline = dict(bound="mfma", achieved=dom["achieved"], peak=PEAK_INT8_TOPS, unit="TFLOP/s", frac=dom["frac"],
+                    traffic=None, kernel=dom["kernel"] + " (" + dom["shape"] + ")",
+                    note="int8 MFMA rate in TOP/s (2 ops per multiply-accumulate); slowest convolution")
+    summary = dict(int8_mfma_util_pct=round(100 * total_ops / (conv_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
+                   conv_gop_per_image=round(total_ops / B / 1e9, 3), sum_kernel_ms=round(sum(k["ms"] for k in kernels), 4))
+
+    cpu_baseline = parity = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        b_sub = min(B, 2)
+        p_sub = W.resnet_params(args.workload, 0, batch=b_sub)
+        c0 = time.perf_counter()
+        want = O.resnet_forward(p_sub)["logits"]
+        cpu_s = time.perf_counter() - c0
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu_baseline = dict(value=round(b_sub / cpu_s, 3), unit="images/s", cores=cores, kind="oracle",
+                            sample=f"one pass of the whole network on {b_sub} of {B} images, {cpu_s:.2f} s")
+        step()
+        torch.cuda.synchronize()
+        got = logits[:b_sub].cpu().numpy()
+        parity = dict(logits_bit_identical=bool(np.array_equal(got.view(np.uint32), want.view(np.uint32))),
+                      max_abs_diff=float(np.abs(got - want).max()),
+                      note=f"fp32 logits of the first {b_sub} images, GPU vs oracle (library-built ReLU table)")
+
+    cfg = p["cfg"]
+    out = dict(metric="PWL encoder-layer sequences/s + int8 MFMA util % + nonlinear-kernel HBM GB/s",
+               value=round(B / (ms_per_step * 1e-3), 1), unit="images/s", n_gpus=1, steps=args.steps,
+               warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="int8 (int32 accumulate, fp32 epilogue)", data="synthetic",
+               config=dict(workload=args.workload, B=B, image=cfg["HW"], stages=list(cfg["stages"]),
+                           widths=list(cfg["widths"]), classes=cfg["classes"]),
+               roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, summary=summary, parity=parity)
     print(json.dumps(out))
 
 

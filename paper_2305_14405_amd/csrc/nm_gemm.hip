@@ -49,6 +49,7 @@ struct GemmParams {
     long ldo;
     int vec_out;
     int q16;       // int8 output rows may be written with 16-byte stores
+    int r16;       // int8 residual rows may be read with 16-byte loads (and N % 16 == 0)
     int vec_cols;  // bias / per-column scale vectors may be read with 16-byte loads
     int8_t* out_q;
     float* out_f32;
@@ -114,7 +115,9 @@ __device__ __forceinline__ v4i load_chunk(const int8_t* __restrict__ X, long ld,
 // Epilogue specialisations: the generic one reads every option at run time; the others fix the
 // set of outputs and options the encoder layer uses, which removes dead code from the unrolled
 // epilogue (it is instantiated once per accumulator group).
-enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4 };
+enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4, EPI_Q_TABLE_RESID = 5 };
+// EPI_Q_TABLE_RESID: int8 residual, table (no input clamp), int8 output: the last convolution of a
+// residual block (sum with the shortcut, ReLU).
 
 struct Epi4 {
     float y[4];
@@ -177,9 +180,9 @@ template <int kEpi>
 __device__ __forceinline__ void epi_math(const GemmParams& p, const float2* s_kb, const int (&a4)[4],
                                          const Col4& c, const int (&r4)[4], Epi4& o)
 {
-    const bool use_resid = kEpi == EPI_GENERIC ? p.resid != nullptr : kEpi == EPI_F32_RESID;
-    const bool use_table = kEpi == EPI_GENERIC ? p.has_table != 0 : kEpi == EPI_Q_TABLE;
-    const bool need_q = kEpi == EPI_GENERIC ? p.out_q != nullptr : (kEpi == EPI_Q || kEpi == EPI_Q_TABLE);
+    const bool use_resid = kEpi == EPI_GENERIC ? p.resid != nullptr : (kEpi == EPI_F32_RESID || kEpi == EPI_Q_TABLE_RESID);
+    const bool use_table = kEpi == EPI_GENERIC ? p.has_table != 0 : (kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID);
+    const bool need_q = kEpi == EPI_GENERIC ? p.out_q != nullptr : (kEpi == EPI_Q || kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID);
 #pragma unroll
     for (int e = 0; e < 4; ++e) { o.y[e] = 0.0f; o.q[e] = 0; o.s[e] = 0; }
     if (kEpi == EPI_ACC) return;
@@ -188,7 +191,7 @@ __device__ __forceinline__ void epi_math(const GemmParams& p, const float2* s_kb
     for (int e = 0; e < 4; ++e) {
         float v = __builtin_fmaf((float)a4[e], c.scale[e], c.bias[e]);
         if (use_resid) v = __builtin_fmaf((float)r4[e], rs, v);
-        if (use_table) v = kEpi == EPI_Q_TABLE ? pwl_eval_noclamp(v, p.table, s_kb, o.s[e]) : pwl_eval(v, p.table, s_kb, o.s[e]);
+        if (use_table) v = (kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID) ? pwl_eval_noclamp(v, p.table, s_kb, o.s[e]) : pwl_eval(v, p.table, s_kb, o.s[e]);
         o.y[e] = v;
         if (need_q) o.q[e] = requant(v, c.inv[e]);
     }
@@ -198,7 +201,7 @@ template <int kEpi>
 __device__ __forceinline__ void epi_store(const GemmParams& p, long rowoff, int nb,
                                           const int (&a4)[4], const Epi4& o, bool vec, bool skip_q)
 {
-    const bool st_q = (kEpi == EPI_GENERIC ? p.out_q != nullptr : (kEpi == EPI_Q || kEpi == EPI_Q_TABLE)) && !skip_q;
+    const bool st_q = (kEpi == EPI_GENERIC ? p.out_q != nullptr : (kEpi == EPI_Q || kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID)) && !skip_q;
     const bool st_f = kEpi == EPI_GENERIC ? p.out_f32 != nullptr : kEpi == EPI_F32_RESID;
     const bool st_a = kEpi == EPI_GENERIC ? p.out_acc != nullptr : kEpi == EPI_ACC;
     const bool st_s = kEpi == EPI_GENERIC && p.dbg_seg && p.has_table;
@@ -553,6 +556,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_k
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
+    // The specialised residual epilogues read the int8 residual rows this wavefront will finish
+    // with 16-byte row loads, issued now so that they travel during the main loop; after it they
+    // pass through the (then free) LDS patch to the lanes that need them.
+    constexpr bool kResid8 = kEpi == EPI_F32_RESID || kEpi == EPI_Q_TABLE_RESID;
+    constexpr int RCPR = WN / 16;                 // 16-byte chunks per residual row of the sub-tile
+    constexpr int RCH = 32 * TMF * RCPR;          // chunks of the rows this wavefront finishes
+    constexpr int RL = (RCH + 63) / 64;
+    v4i rpre[RL];
+    const bool resid_rows = kResid8 && p.r16;     // uniform
+    if (resid_rows) {
+#pragma unroll
+        for (int t = 0; t < RL; ++t) {
+            const int c = lane + 64 * t;
+            rpre[t] = v4i{0, 0, 0, 0};
+            if (c < RCH) {
+                const int mr = m0 + wave_m + 32 * (kg * TMF) + c / RCPR, n = n0 + wave_n + 16 * (c % RCPR);
+                if (mr < p.M && n + 15 < p.N)
+                    rpre[t] = *reinterpret_cast<const v4i*>(p.resid + obase + (long)mr * p.ldo + n);
+            }
+        }
+    }
+
     const int nk = p.K / BK;
 #pragma unroll
     for (int st = 0; st < kStages - 1; ++st)
@@ -630,12 +655,33 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_k
     const int row_blk0 = kg * TMF;  // first 32-row block of the sub-tile this wavefront finishes
 
     // ---- epilogue ------------------------------------------------------------------------------
-    const bool patch_q = (kEpi == EPI_GENERIC || kEpi == EPI_Q || kEpi == EPI_Q_TABLE) &&
+    const bool patch_q = (kEpi == EPI_GENERIC || kEpi == EPI_Q || kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID) &&
                          p.out_q != nullptr && p.q16;  // uniform: int8 rows leave through LDS
     int8_t* patch = smem + wave_t * (WM * SW);
     // the specialised residual epilogue fetches all of the lane's residual words up front
     unsigned resw[TMF][TN][4];
-    if (kEpi == EPI_F32_RESID) {
+    if (resid_rows) {
+#pragma unroll
+        for (int t = 0; t < RL; ++t) {
+            const int c = lane + 64 * t;
+            if (c < RCH) *reinterpret_cast<v4i*>(patch + (32 * row_blk0 + c / RCPR) * SW + 16 * (c % RCPR)) = rpre[t];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int i = 0; i < TMF; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    resw[i][j][g] = *reinterpret_cast<const unsigned*>(
+                        patch + (32 * (row_blk0 + i) + frag_row) * SW + 32 * j + 8 * g + 4 * frag_half);
+        // the patch is reused for the output rows: every lane's reads come first
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else if (kEpi == EPI_F32_RESID || kEpi == EPI_Q_TABLE_RESID) {
 #pragma unroll
         for (int i = 0; i < TMF; ++i)
 #pragma unroll
@@ -682,7 +728,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_k
 #pragma unroll
                     for (int e = 0; e < 4; ++e) a4[e] = fin[i][j][4 * g + e];
                     int r4[4] = {0, 0, 0, 0};
-                    if (kEpi == EPI_F32_RESID) {
+                    if (kEpi == EPI_F32_RESID || kEpi == EPI_Q_TABLE_RESID) {
                         if (kFullTile || nb + 3 < p.N) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e) r4[e] = (int)(int8_t)(resw[i][j][g] >> (8 * e));
@@ -762,6 +808,7 @@ static int32_t launch_stream(GemmParams& p, int epi, int batches, size_t table_b
     case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q>(p, batches, table_bytes, s);
     case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q_TABLE>(p, batches, table_bytes, s);
     case EPI_F32_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_F32_RESID>(p, batches, table_bytes, s);
+    case EPI_Q_TABLE_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q_TABLE_RESID>(p, batches, table_bytes, s);
     case EPI_ACC: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_ACC>(p, batches, table_bytes, s);
     default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_GENERIC>(p, batches, table_bytes, s);
     }
@@ -774,6 +821,7 @@ static int32_t launch_stream_conv(GemmParams& p, int epi, size_t table_bytes, hi
     switch (epi) {
     case EPI_Q: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q, true>(p, 1, table_bytes, s);
     case EPI_Q_TABLE: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q_TABLE, true>(p, 1, table_bytes, s);
+    case EPI_Q_TABLE_RESID: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_Q_TABLE_RESID, true>(p, 1, table_bytes, s);
     default: return launch_stream_epi<BM, BN, WAVES_M, WAVES_N, KSPLIT, BK, kStages, EPI_GENERIC, true>(p, 1, table_bytes, s);
     }
 }
@@ -806,6 +854,7 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
                 (!g.out_q || aligned(g.out_q, 4)) && (!g.out_f32 || aligned(g.out_f32, 16)) &&
                 (!g.out_acc || aligned(g.out_acc, 16)) && (!g.dbg_seg || aligned(g.dbg_seg, 8)) &&
                 (!g.resid || aligned(g.resid, 4));
+    p.r16 = g.resid && aligned(g.resid, 16) && g.ldo % 16 == 0 && g.o_outer % 16 == 0 && g.o_inner % 16 == 0 && g.N % 16 == 0;
     p.q16 = g.out_q && aligned(g.out_q, 16) && g.ldo % 16 == 0 && g.o_outer % 16 == 0 && g.o_inner % 16 == 0;
 
     const size_t table_bytes = g.has_table ? sizeof(float2) * (size_t)g.table.nseg : 0;
@@ -820,6 +869,7 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         // EPI_Q_TABLE is compiled without the input clamp; a table with that flag takes the generic epilogue
         if (only_q && !g.resid) epi = !g.has_table ? EPI_Q : g.table.clamp_input ? EPI_GENERIC : EPI_Q_TABLE;
         else if (g.out_f32 && !g.out_q && !g.out_acc && g.resid && !g.has_table && p.vec_out) epi = EPI_F32_RESID;
+        else if (only_q && g.resid && g.has_table && !g.table.clamp_input && p.vec_out) epi = EPI_Q_TABLE_RESID;
         else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
     }
     if (g.conv) {
@@ -828,6 +878,7 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         if (!w_al || !aligned(g.A, 16) || g.cCin % 64 != 0 || g.K != g.cCin * g.cKw * (g.K / (g.cCin * g.cKw)))
             return fail(NM_ERR_UNSUPPORTED, "conv gemm: operands not aligned for the gathered loader");
         if (g.N <= 64) rc = launch_stream_conv<256, 64, 4, 1, 1, 64, 4>(p, epi, table_bytes, stream);
+        else if (g.K <= 256) rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 2>(p, epi, table_bytes, stream);
         else if (g.cCin % 128 == 0 && table_bytes <= 32768) rc = launch_stream_conv<128, 128, 2, 2, 2, 128, 3>(p, epi, table_bytes, stream);
         else rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 3>(p, epi, table_bytes, stream);
         if (rc) return rc;
@@ -835,7 +886,13 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     }
     const bool stream_ok = al && !g.w_is_kn && g.K % 64 == 0 && !force_generic();
     const bool k128 = g.K % 128 == 0;  // 128-byte k-slices (whole L2 lines) fetch ~1.5x faster than 64-byte ones
-    if (stream_ok && k128 && g.N >= 1536 && g.M >= 256 && !force_mid_tile()) {
+    if (stream_ok && g.K <= 256 && g.N > 64 && g.M >= 4096) {
+        // short contraction, many rows (the 1x1 convolutions of a residual CNN): the kernel is all
+        // prologue and epilogue, so a small two-stage ring lets four workgroups share a CU and overlap
+        rc = launch_stream<128, 128, 2, 2, 1, 64, 2>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && g.K <= 128 && g.N > 32 && g.N <= 64 && g.M >= 4096) {
+        rc = launch_stream<256, 64, 4, 1, 1, 64, 2>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && k128 && g.N >= 1536 && g.M >= 256 && !force_mid_tile()) {
         rc = launch_stream<256, 192, 4, 2, 1, 128, 2>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && k128 && g.N > 64 && table_bytes <= 32768) {
         // few workgroups per CU: two wavefronts per sub-tile (k-steps split) keep every SIMD busy
