@@ -872,36 +872,44 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         else if (only_q && g.resid && g.has_table && !g.table.clamp_input && p.vec_out) epi = EPI_Q_TABLE_RESID;
         else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
     }
+    // Tile configuration.  BIG (256x192, two 128-byte stages) when the output is wide and its tiles
+    // fill the chip; several small workgroups per CU (MID2 / MID3: 128x128, 64-byte slices, two or
+    // three stages, 32 / 48 KB of LDS) when there are at least three 128x128 tiles per CU, so that
+    // one workgroup's epilogue overlaps another's loads; SPLIT (128x128, two wavefronts per
+    // sub-tile, 128-byte slices) when tiles are scarce; NARROW (256x64) for outputs of at most 64 columns.
+    const bool k128 = g.K % 128 == 0 && (!g.conv || g.cCin % 128 == 0);  // 128-byte k-slices fetch ~1.5x faster
+    const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 191) / 192) * batches;
+    const long mid_tiles = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * batches;
+    enum { CFG_BIG, CFG_SPLIT, CFG_MID3, CFG_MID2, CFG_NARROW } cfg;
+    if (g.N <= 64) cfg = CFG_NARROW;
+    else if (!g.conv && k128 && g.N >= 1536 && big_tiles >= 192 && !force_mid_tile()) cfg = CFG_BIG;
+    else if (mid_tiles >= 768 && !force_mid_tile()) cfg = g.K <= 256 ? CFG_MID2 : CFG_MID3;
+    else if (k128 && table_bytes <= 32768) cfg = CFG_SPLIT;
+    else cfg = CFG_MID3;
     if (g.conv) {
         // gathered A operand: streaming kernel only (the caller has checked Cin % 64 == 0, 16-byte
         // aligned image and weights); one problem, no batching
-        if (!w_al || !aligned(g.A, 16) || g.cCin % 64 != 0 || g.K != g.cCin * g.cKw * (g.K / (g.cCin * g.cKw)))
+        if (!w_al || !aligned(g.A, 16) || g.cCin % 64 != 0 || g.K % (g.cCin * g.cKw) != 0)
             return fail(NM_ERR_UNSUPPORTED, "conv gemm: operands not aligned for the gathered loader");
-        if (g.N <= 64) rc = launch_stream_conv<256, 64, 4, 1, 1, 64, 4>(p, epi, table_bytes, stream);
-        else if (g.K <= 256) rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 2>(p, epi, table_bytes, stream);
-        else if (g.cCin % 128 == 0 && table_bytes <= 32768) rc = launch_stream_conv<128, 128, 2, 2, 2, 128, 3>(p, epi, table_bytes, stream);
+        if (cfg == CFG_NARROW) rc = launch_stream_conv<256, 64, 4, 1, 1, 64, 2>(p, epi, table_bytes, stream);
+        else if (cfg == CFG_MID2) rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 2>(p, epi, table_bytes, stream);
+        else if (cfg == CFG_SPLIT) rc = launch_stream_conv<128, 128, 2, 2, 2, 128, 3>(p, epi, table_bytes, stream);
         else rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 3>(p, epi, table_bytes, stream);
         if (rc) return rc;
         return check_hip(hipGetLastError(), "conv gemm launch");
     }
     const bool stream_ok = al && !g.w_is_kn && g.K % 64 == 0 && !force_generic();
-    const bool k128 = g.K % 128 == 0;  // 128-byte k-slices (whole L2 lines) fetch ~1.5x faster than 64-byte ones
-    if (stream_ok && g.K <= 256 && g.N > 64 && g.M >= 4096) {
-        // short contraction, many rows (the 1x1 convolutions of a residual CNN): the kernel is all
-        // prologue and epilogue, so a small two-stage ring lets four workgroups share a CU and overlap
-        rc = launch_stream<128, 128, 2, 2, 1, 64, 2>(p, epi, batches, table_bytes, stream);
-    } else if (stream_ok && g.K <= 128 && g.N > 32 && g.N <= 64 && g.M >= 4096) {
-        rc = launch_stream<256, 64, 4, 1, 1, 64, 2>(p, epi, batches, table_bytes, stream);
-    } else if (stream_ok && k128 && g.N >= 1536 && g.M >= 256 && !force_mid_tile()) {
+    if (stream_ok && cfg == CFG_BIG) {
         rc = launch_stream<256, 192, 4, 2, 1, 128, 2>(p, epi, batches, table_bytes, stream);
-    } else if (stream_ok && k128 && g.N > 64 && table_bytes <= 32768) {
-        // few workgroups per CU: two wavefronts per sub-tile (k-steps split) keep every SIMD busy
+    } else if (stream_ok && cfg == CFG_MID2) {
+        rc = launch_stream<128, 128, 2, 2, 1, 64, 2>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && cfg == CFG_SPLIT) {
         rc = launch_stream<128, 128, 2, 2, 2, 128, 3>(p, epi, batches, table_bytes, stream);
-    } else if (stream_ok && g.N > 64) {
+    } else if (stream_ok && cfg == CFG_MID3) {
         rc = launch_stream<128, 128, 2, 2, 1, 64, 3>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && g.N > 32 && g.M >= 1024) {
         // narrow outputs with many rows (the 64-channel convolutions of a residual CNN)
-        rc = launch_stream<256, 64, 4, 1, 1, 64, 4>(p, epi, batches, table_bytes, stream);
+        rc = launch_stream<256, 64, 4, 1, 1, 64, 2>(p, epi, batches, table_bytes, stream);
     } else if (g.N <= 64) {
         p.tiles_m = (g.M + 127) / 128; p.tiles_n = (g.N + 63) / 64;
         launch_cfg<128, 64, 32, 64>(p, al, g.w_is_kn, dim3(p.tiles_m * p.tiles_n, batches), table_bytes, stream);
