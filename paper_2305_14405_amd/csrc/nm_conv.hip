@@ -8,7 +8,7 @@
 //    gathers the rows of the patch matrix straight from the image while loading its A operand
 //    (no patch matrix in memory);
 //  * anything else (the 3-channel stem, odd channel counts): a small kernel writes the patch
-//    matrix [B*Ho*Wo, K16] (K rounded up to 16, zero filled) into the caller's workspace and the
+//    matrix [B*Ho*Wo, K16] (K rounded up to 64, zero filled) into the caller's workspace and the
 //    GEMM runs on it.
 #include "nm_device.h"
 
@@ -17,7 +17,8 @@ namespace nm {
 constexpr int kConvThreads = 256;
 
 // Patch matrix: row m = (b, ho, wo), column k = (tap i, tap j, channel c), zeros in the padding
-// and in the columns K .. K16-1.  One thread writes 16 consecutive columns of one row.
+// and in the columns K .. K16-1 (K16: K rounded up to 64).  One thread writes 16 consecutive
+// columns of one row.
 __global__ __launch_bounds__(kConvThreads) void im2col_kernel(
     const int8_t* __restrict__ x, int H, int W, int Cin, int kw, int stride, int pad, int Ho, int Wo,
     int K, int K16, long rows, int8_t* __restrict__ out)
@@ -30,17 +31,19 @@ __global__ __launch_bounds__(kConvThreads) void im2col_kernel(
         const int wo = (int)(m % Wo), ho = (int)((m / Wo) % Ho);
         const long b = m / ((long)Wo * Ho);
         unsigned word[4] = {0, 0, 0, 0};
+        // (tap row, tap column, channel) of column k0, then stepped along the 16 columns
+        int c = k0 % Cin, tap = k0 / Cin;
+        int ti = tap / kw, tj = tap % kw;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const int k = k0 + e;
             int v = 0;
-            if (k < K) {
-                const int c = k % Cin, tap = k / Cin;
-                const int hi = ho * stride - pad + tap / kw, wi = wo * stride - pad + tap % kw;
+            if (k0 + e < K) {
+                const int hi = ho * stride - pad + ti, wi = wo * stride - pad + tj;
                 if ((unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W)
                     v = x[((b * H + hi) * W + wi) * Cin + c];
             }
             word[e >> 2] |= (unsigned)(v & 0xff) << (8 * (e & 3));
+            if (++c == Cin) { c = 0; if (++tj == kw) { tj = 0; ++ti; } }
         }
         *reinterpret_cast<v4i*>(out + m * K16 + k0) = v4i{(int)word[0], (int)word[1], (int)word[2], (int)word[3]};
     }
@@ -98,6 +101,144 @@ __global__ __launch_bounds__(kConvThreads) void avgpool_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Direct convolution for images with at most four channels (the stem of a CNN: 7x7, stride 2,
+// three channels).  A patch matrix would be 50 times the image; instead a workgroup stages the
+// part of the image its 16 x 16 output positions need in LDS, one 4-byte pixel per position
+// (missing channels and everything outside the image are zero), and the filter as rows of 32
+// bytes per filter row (kw <= 8 pixels of 4 bytes, zero filled).  One MFMA k-step is then one
+// filter row: the operand bytes of output position (ho, wo) are 32 consecutive LDS bytes starting
+// at pixel (ho*stride + i, wo*stride); bytes beyond the kw-th pixel meet zero filter bytes.
+// Accumulators and epilogue arithmetic are those of the matrix product (exact integers, the same
+// fp32 operations), so the result is bit-identical to the other routes.
+// A wavefront owns 4 rows x 16 columns of positions and all (up to 64) output channels.
+// ---------------------------------------------------------------------------------------------
+struct StemParams {
+    const int8_t* x; const int8_t* w;
+    const float* bias; const float* alpha_vec;
+    float alpha, out_inv_scale;
+    int has_table;
+    DevTable table;
+    int B, H, W, Cin, Cout, kh, kw, stride, pad, Ho, Wo;
+    int prow, pcol, pitch;   // staged image patch: rows, pixels per row, bytes per row
+    int8_t* out_q;
+};
+
+__global__ __launch_bounds__(256) void stem_conv_kernel(StemParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+    int8_t* sX = smem;                                   // [prow][pitch]
+    int8_t* sW = smem + p.prow * p.pitch;                // [64][kh][32]
+    int8_t* sO = sW + 64 * p.kh * 32;                    // [4 wavefronts][64 positions][80]
+    float* s_cols = reinterpret_cast<float*>(sO + 4 * 64 * 80);   // scale | bias, 64 each
+    float2* s_kb = reinterpret_cast<float2*>(s_cols + 128);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles_w = (p.Wo + 15) / 16;
+    const int ho0 = (blockIdx.x / tiles_w) * 16, wo0 = (blockIdx.x % tiles_w) * 16;
+    const long b = blockIdx.y;
+    const int hi0 = ho0 * p.stride - p.pad, wi0 = wo0 * p.stride - p.pad;
+
+    if (p.has_table) stage_table(s_kb, p.table);
+    if (tid < 64) {
+        s_cols[tid] = tid < p.Cout ? (p.alpha_vec ? p.alpha_vec[tid] : p.alpha) : 0.0f;
+        s_cols[64 + tid] = (tid < p.Cout && p.bias) ? p.bias[tid] : 0.0f;
+    }
+    // image patch: one dword per pixel
+    for (int idx = tid; idx < p.prow * p.pcol; idx += 256) {
+        const int r = idx / p.pcol, c = idx % p.pcol;
+        const int hi = hi0 + r, wi = wi0 + c;
+        unsigned px = 0;
+        if ((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W) {
+            const int8_t* src = p.x + ((b * p.H + hi) * p.W + wi) * p.Cin;
+            for (int ch = 0; ch < p.Cin; ++ch) px |= (unsigned)(uint8_t)src[ch] << (8 * ch);
+        }
+        *reinterpret_cast<unsigned*>(sX + r * p.pitch + 4 * c) = px;
+    }
+    // zero the slack at the end of every patch row (read by the last positions' 32-byte windows)
+    for (int idx = tid; idx < p.prow * ((p.pitch - 4 * p.pcol) / 4); idx += 256) {
+        const int per = (p.pitch - 4 * p.pcol) / 4;
+        *reinterpret_cast<unsigned*>(sX + (idx / per) * p.pitch + 4 * p.pcol + 4 * (idx % per)) = 0u;
+    }
+    // filter: [n][i][8 pixels of 4 bytes]
+    for (int idx = tid; idx < 64 * p.kh * 8; idx += 256) {
+        const int j = idx % 8, i = (idx / 8) % p.kh, n = idx / (8 * p.kh);
+        unsigned px = 0;
+        if (n < p.Cout && j < p.kw) {
+            const int8_t* src = p.w + (((long)n * p.kh + i) * p.kw + j) * p.Cin;
+            for (int ch = 0; ch < p.Cin; ++ch) px |= (unsigned)(uint8_t)src[ch] << (8 * ch);
+        }
+        *reinterpret_cast<unsigned*>(sW + (n * p.kh + i) * 32 + 4 * j) = px;
+    }
+    __syncthreads();
+
+    // lane (m, half): position m of a 32-position block; block t covers wavefront rows 2t, 2t+1
+    const int fr = lane & 31, half = lane >> 5;
+    v16i acc[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][j][v] = 0;
+    int offA[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int pr = wave * 4 + 2 * t + (fr >> 4), pc = fr & 15;   // position inside the 16 x 16 tile
+        offA[t] = pr * p.stride * p.pitch + pc * p.stride * 4 + 16 * half;
+    }
+    for (int i = 0; i < p.kh; ++i) {
+        v4i fa[2], fw[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int8_t* a = sX + offA[t] + i * p.pitch;   // 4-byte aligned
+            const unsigned* a4 = reinterpret_cast<const unsigned*>(a);
+            fa[t] = v4i{(int)a4[0], (int)a4[1], (int)a4[2], (int)a4[3]};
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            fw[j] = *reinterpret_cast<const v4i*>(sW + ((32 * j + fr) * p.kh + i) * 32 + 16 * half);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[t][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fa[t], acc[t][j], 0, 0, 0);
+    }
+
+    // epilogue: lane (m, half) holds, per group g of four registers, channels 32j + 8g + 4half .. +3
+    int8_t* patch = sO + wave * (64 * 80);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = 32 * j + 8 * g + 4 * half;
+                const v4f sc = *reinterpret_cast<const v4f*>(s_cols + n);
+                const v4f bi = *reinterpret_cast<const v4f*>(s_cols + 64 + n);
+                int q[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = __builtin_fmaf((float)acc[t][j][4 * g + e], sc[e], bi[e]);
+                    if (p.has_table) { int sg; v = pwl_eval(v, p.table, s_kb, sg); }
+                    q[e] = requant(v, p.out_inv_scale);
+                }
+                *reinterpret_cast<unsigned*>(patch + (32 * t + fr) * 80 + n) = pack4(q[0], q[1], q[2], q[3]);
+            }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // 16-byte stores: position rows of Cout bytes are contiguous along wo
+    const int chunks = p.Cout / 16;
+    for (int c = lane; c < 64 * chunks; c += 64) {
+        const int pos = c / chunks, cc = c % chunks;
+        const int ho = ho0 + wave * 4 + (pos >> 4), wo = wo0 + (pos & 15);
+        if (ho < p.Ho && wo < p.Wo)
+            *reinterpret_cast<v4i*>(p.out_q + ((b * p.Ho + ho) * p.Wo + wo) * p.Cout + 16 * cc) =
+                *reinterpret_cast<const v4i*>(patch + pos * 80 + 16 * cc);
+    }
+}
+
 static int grid_for(long units)
 {
     long b = (units + kConvThreads - 1) / kConvThreads;
@@ -108,7 +249,7 @@ static int grid_for(long units)
 struct ConvPlan {
     int Ho, Wo, K, K16;
     long M;
-    int route;  // 0: plain matrix, 1: gathered operand, 2: patch matrix in the workspace
+    int route;  // 0: plain matrix, 1: gathered operand, 2: patch matrix in the workspace, 3: direct (few channels)
     size_t ws_bytes;
 };
 
@@ -129,11 +270,15 @@ static int32_t plan_conv(const nm_conv_desc* d, const char* what, ConvPlan* pl)
         return fail(NM_ERR_UNSUPPORTED, "%s: tensor too large", what);
     if (M >= (1LL << 31)) return fail(NM_ERR_UNSUPPORTED, "%s: more than 2^31 output positions", what);
     pl->K = (int)K;
-    pl->K16 = (int)((K + 15) / 16 * 16);
+    pl->K16 = (int)((K + 63) / 64 * 64);  // whole 64-byte k-slices: the streaming GEMM runs on the patch matrix
     pl->M = (long)M;
     const bool plain = d->kh == 1 && d->kw == 1 && d->stride == 1 && d->pad == 0;
     const bool gather = d->Cin % 64 == 0 && aligned(d->x, 16) && aligned(d->w, 16);
-    pl->route = plain ? 0 : gather ? 1 : 2;
+    // direct kernel: few input channels, a filter row fits 32 bytes, int8 output only
+    const bool direct = !plain && d->Cin <= 4 && d->kw <= 8 && d->Cout <= 64 && d->Cout % 16 == 0 && d->out_q &&
+                        !d->out_f32 && !d->dbg_acc && !d->resid && aligned(d->out_q, 16) &&
+                        15 * d->stride + d->kh <= 64 && d->B <= 65535;
+    pl->route = plain ? 0 : gather ? 1 : direct ? 3 : 2;
     pl->ws_bytes = pl->route == 2 ? (size_t)M * pl->K16 + (size_t)d->Cout * pl->K16 : 0;
     return NM_OK;
 }
@@ -187,6 +332,25 @@ int32_t nm_conv2d_pwl(const nm_conv_desc* d, void* ws, size_t ws_bytes, void* st
     g.out_inv_scale = d->out_inv_scale;
     g.ldo = d->Cout;
     g.out_q = d->out_q; g.out_f32 = d->out_f32; g.out_acc = d->dbg_acc;
+    if (pl.route == 3) {
+        StemParams sp{};
+        sp.x = d->x; sp.w = d->w; sp.bias = d->bias; sp.alpha_vec = d->alpha_vec; sp.alpha = d->alpha;
+        sp.out_inv_scale = d->out_inv_scale; sp.has_table = g.has_table; sp.table = g.table;
+        sp.B = d->B; sp.H = d->H; sp.W = d->W; sp.Cin = d->Cin; sp.Cout = d->Cout; sp.kh = d->kh; sp.kw = d->kw;
+        sp.stride = d->stride; sp.pad = d->pad; sp.Ho = pl.Ho; sp.Wo = pl.Wo;
+        sp.prow = 15 * d->stride + d->kh;
+        sp.pcol = 15 * d->stride + d->kw;
+        // a position's window is 32 bytes from its first pixel: the last position's reaches 8 pixels
+        sp.pitch = ((15 * d->stride + 8) * 4 + 15) / 16 * 16;
+        if (sp.pitch < 4 * sp.pcol) sp.pitch = (4 * sp.pcol + 15) / 16 * 16;
+        sp.out_q = d->out_q;
+        const size_t shmem = (size_t)sp.prow * sp.pitch + 64 * (size_t)d->kh * 32 + 4 * 64 * 80 + 128 * sizeof(float) +
+                             (g.has_table ? sizeof(float2) * (size_t)g.table.nseg : 0);
+        if (shmem > 64 * 1024) return fail(NM_ERR_UNSUPPORTED, "nm_conv2d_pwl: direct route needs %zu bytes of LDS", shmem);
+        const dim3 grid(((pl.Ho + 15) / 16) * ((pl.Wo + 15) / 16), d->B);
+        hipLaunchKernelGGL(stem_conv_kernel, grid, dim3(256), shmem, stream, sp);
+        return check_hip(hipGetLastError(), "nm_conv2d_pwl direct launch");
+    }
     if (pl.route == 0) {
         g.A = d->x; g.lda = d->Cin;
     } else if (pl.route == 1) {

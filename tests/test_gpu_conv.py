@@ -112,7 +112,7 @@ def test_conv_validation_and_empty():
     o = torch.zeros((1, 8, 8, 4), dtype=torch.int8, device=DEV)
     d = nm.make_conv_desc(x, w, 1, 1, tables=dt, table_idx=0, out_q=o)
     need = nm.nm_conv2d_workspace(d)
-    assert need == 64 * 32 + 4 * 32
+    assert need == 64 * 64 + 4 * 64  # patch matrix and filter rows, K = 27 padded to 64
     with pytest.raises(nm.NmError) as ei:
         nm.nm_conv2d_pwl(d, None)
     assert ei.value.status == nm.NM_ERR_WORKSPACE
