@@ -146,3 +146,52 @@ def test_compute_entry_points_validate_before_launch(lib):
     assert b"layer 2" in lib.nm_last_error()
     ld.heads = 7
     assert lib.nm_encoder_layer_workspace(C.byref(ld), C.byref(n)) == nm.NM_ERR_INVALID_ARG
+
+
+def test_conv_and_pool_entry_points_validate_before_launch(lib):
+    """nm_conv2d_workspace / nm_conv2d_pwl / pooling: geometry and pointer checks happen on the
+    host before any HIP call; the workspace size follows the route the shape takes."""
+    z = C.c_void_p(0)
+    one = C.c_void_p(256)
+    n = C.c_size_t()
+    d = nm.ConvDesc()
+    assert lib.nm_conv2d_workspace(None, C.byref(n)) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_conv2d_workspace(C.byref(d), C.byref(n)) == nm.NM_ERR_INVALID_ARG   # all zero
+    d.B, d.H, d.W, d.Cin, d.Cout, d.kh, d.kw, d.stride, d.pad = 2, 8, 8, 3, 4, 3, 3, 1, 1
+    d.table_idx = -1
+    assert lib.nm_conv2d_workspace(C.byref(d), None) == nm.NM_ERR_INVALID_ARG
+    # odd channel count: patch matrix (K = 27 -> 64 bytes per row) plus the padded filter rows
+    assert lib.nm_conv2d_workspace(C.byref(d), C.byref(n)) == nm.NM_OK
+    assert n.value == 2 * 8 * 8 * 64 + 4 * 64
+    assert lib.nm_conv2d_pwl(C.byref(d), None, 0, z) == nm.NM_ERR_INVALID_ARG        # no output
+    d.out_q = 256
+    assert lib.nm_conv2d_pwl(C.byref(d), None, 0, z) == nm.NM_ERR_INVALID_ARG        # NULL x / w
+    d.x, d.w = 256, 256
+    assert lib.nm_conv2d_pwl(C.byref(d), None, 0, z) == nm.NM_ERR_WORKSPACE
+    assert lib.nm_conv2d_pwl(C.byref(d), one, 16, z) == nm.NM_ERR_WORKSPACE          # too small
+    assert b"workspace" in lib.nm_last_error()
+    d.table_idx = 0                                                                    # table without tables
+    assert lib.nm_conv2d_pwl(C.byref(d), one, n, z) == nm.NM_ERR_INVALID_ARG
+    d.table_idx = -1
+    # a 1x1 / stride 1 convolution and a 64-channel 3x3 convolution need no workspace
+    d.Cin, d.kh, d.kw, d.pad = 3, 1, 1, 0
+    assert lib.nm_conv2d_workspace(C.byref(d), C.byref(n)) == nm.NM_OK and n.value == 0
+    d.Cin, d.kh, d.kw, d.pad = 64, 3, 3, 1
+    assert lib.nm_conv2d_workspace(C.byref(d), C.byref(n)) == nm.NM_OK and n.value == 0
+    d.kh, d.kw, d.pad = 9, 9, 0                                                        # filter larger than the image
+    assert lib.nm_conv2d_workspace(C.byref(d), C.byref(n)) == nm.NM_ERR_INVALID_ARG
+    d.kh, d.kw, d.Cin = 40, 40, 64                                                     # kh*kw*Cin > 65536
+    d.H = d.W = 64
+    assert lib.nm_conv2d_workspace(C.byref(d), C.byref(n)) == nm.NM_ERR_UNSUPPORTED
+    d.B = 0                                                                            # empty batch: nothing to do
+    d.kh = d.kw = 3
+    assert lib.nm_conv2d_pwl(C.byref(d), None, 0, z) == nm.NM_OK
+    # pooling
+    assert lib.nm_maxpool_i8(one, 1, 8, 8, 4, 3, 2, 3, one, z) == nm.NM_ERR_INVALID_ARG      # pad >= k
+    assert lib.nm_maxpool_i8(one, 1, 8, 8, 4, 0, 2, 0, one, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_maxpool_i8(None, 1, 8, 8, 4, 3, 2, 1, one, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_maxpool_i8(None, 0, 8, 8, 4, 3, 2, 1, None, z) == nm.NM_OK
+    assert lib.nm_avgpool_i8(one, 1, 49, 8, 1.0, 1.0, None, None, z) == nm.NM_ERR_INVALID_ARG  # no output
+    assert lib.nm_avgpool_i8(one, 1, 0, 8, 1.0, 1.0, one, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_avgpool_i8(None, 1, 49, 8, 1.0, 1.0, one, None, z) == nm.NM_ERR_INVALID_ARG
+    assert lib.nm_avgpool_i8(one, 1, 1 << 24, 8, 1.0, 1.0, one, None, z) == nm.NM_ERR_UNSUPPORTED
