@@ -199,6 +199,15 @@ int32_t nm_layernorm_pwl(const float* in, const float* gamma, const float* beta,
                          float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* dbg_seg,
                          void* stream);
 
+/*
+ * nm_layernorm_pwl2: the same with the two functions the paper's list names instead of one rsqrt
+ * table: sd = PWL_sqrt(var + eps); r = PWL_recip(sd).  dbg_seg_sqrt / dbg_seg_recip: [rows].
+ */
+int32_t nm_layernorm_pwl2(const float* in, const float* gamma, const float* beta, float eps,
+                          int64_t rows, int32_t cols, const nm_tables* tables, int32_t sqrt_idx,
+                          int32_t recip_idx, float out_inv_scale, int8_t* out_q, float* out_f32,
+                          uint16_t* dbg_seg_sqrt, uint16_t* dbg_seg_recip, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * nm_pwl_apply: the stand-alone element-wise PWL calculation over a flat buffer (Section 3: an
  * operator that is piecewise linear is evaluated by finding each element's segment, gathering k

@@ -428,9 +428,10 @@ int nmo_softmax_pwl(const void* in, int32_t in_dtype, float alpha, int64_t rows,
  *   r   = PWL_rsqrt(u)
  *   y_j = fmaf(d_j * r, gamma_j, beta_j)
  */
-int nmo_layernorm_pwl(const float* in, const float* gamma, const float* beta, float eps,
-                      int64_t rows, int32_t cols, const nmo_table* t_rsqrt, float out_inv_scale,
-                      int8_t* out_q, float* out_f32, uint16_t* dbg_seg)
+static int layernorm_core(const float* in, const float* gamma, const float* beta, float eps,
+                          int64_t rows, int32_t cols, const nmo_table* t_rsqrt, const nmo_table* t_recip,
+                          float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* dbg_seg,
+                          uint16_t* dbg_seg2)
 {
     if (!in || !gamma || !beta || !t_rsqrt || rows < 0 || cols < 1) return NMO_ERR_ARG;
     const float inv_L = (float)(1.0 / (double)cols);
@@ -446,8 +447,13 @@ int nmo_layernorm_pwl(const float* in, const float* gamma, const float* beta, fl
         float var = canonical_sum(d, cols, 1) * inv_L;
         float u = var + eps;
         int32_t s;
-        float rs = pwl_eval(u, t_rsqrt, &s);
+        float rs = pwl_eval(u, t_rsqrt, &s);   /* rsqrt table, or sqrt table when t_recip is given */
         if (dbg_seg) dbg_seg[r] = (uint16_t)s;
+        if (t_recip) {
+            int32_t s2;
+            rs = pwl_eval(rs, t_recip, &s2);
+            if (dbg_seg2) dbg_seg2[r] = (uint16_t)s2;
+        }
         for (int32_t j = 0; j < cols; ++j) {
             float y = fmaf(d[j] * rs, gamma[j], beta[j]);
             if (out_f32) out_f32[base + j] = y;
@@ -456,6 +462,28 @@ int nmo_layernorm_pwl(const float* in, const float* gamma, const float* beta, fl
         free(d);
     }
     return err ? NMO_ERR_ALLOC : NMO_OK;
+}
+
+int nmo_layernorm_pwl(const float* in, const float* gamma, const float* beta, float eps,
+                      int64_t rows, int32_t cols, const nmo_table* t_rsqrt, float out_inv_scale,
+                      int8_t* out_q, float* out_f32, uint16_t* dbg_seg)
+{
+    return layernorm_core(in, gamma, beta, eps, rows, cols, t_rsqrt, NULL, out_inv_scale, out_q, out_f32,
+                          dbg_seg, NULL);
+}
+
+/*
+ * The variant with the two functions the paper's list names (square root and reciprocal) instead of
+ * one rsqrt table: sd = PWL_sqrt(var + eps); r = PWL_recip(sd); everything else as above.
+ */
+int nmo_layernorm_pwl2(const float* in, const float* gamma, const float* beta, float eps,
+                       int64_t rows, int32_t cols, const nmo_table* t_sqrt, const nmo_table* t_recip,
+                       float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* dbg_seg_sqrt,
+                       uint16_t* dbg_seg_recip)
+{
+    if (!t_recip) return NMO_ERR_ARG;
+    return layernorm_core(in, gamma, beta, eps, rows, cols, t_sqrt, t_recip, out_inv_scale, out_q, out_f32,
+                          dbg_seg_sqrt, dbg_seg_recip);
 }
 
 /* ------------------------------------------------------------------------------------------- */

@@ -115,6 +115,9 @@ def lib() -> C.CDLL:
             L.nmo_layernorm_pwl.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                             C.c_int64, C.c_int32, C.POINTER(CTable), C.c_float,
                                             C.c_void_p, C.c_void_p, C.c_void_p]
+            L.nmo_layernorm_pwl2.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
+                                             C.c_int64, C.c_int32, C.POINTER(CTable), C.POINTER(CTable),
+                                             C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
             L.nmo_gemm_pwl.argtypes = [C.POINTER(CGemm)]
             L.nmo_conv2d_pwl.argtypes = [C.POINTER(CConv)]
             L.nmo_maxpool_i8.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p]
@@ -276,6 +279,21 @@ def layernorm_pwl(x, gamma, beta, eps, t_rsqrt: Table, out_inv_scale):
     _check(lib().nmo_layernorm_pwl(_p(x), _p(gamma), _p(beta), eps, rows, cols, t_rsqrt.ref(),
                                    out_inv_scale, _p(q), _p(y), _p(s)), "layernorm_pwl")
     return dict(y=y, q=q, seg=s)
+
+
+def layernorm_pwl2(x, gamma, beta, eps, t_sqrt: Table, t_recip: Table, out_inv_scale):
+    """LayerNorm with a square-root table followed by a reciprocal table."""
+    x = _arr(x, np.float32)
+    gamma = _arr(gamma, np.float32)
+    beta = _arr(beta, np.float32)
+    rows, cols = x.shape
+    y = np.empty((rows, cols), np.float32)
+    q = np.empty((rows, cols), np.int8)
+    s1 = np.empty(rows, np.uint16)
+    s2 = np.empty(rows, np.uint16)
+    _check(lib().nmo_layernorm_pwl2(_p(x), _p(gamma), _p(beta), eps, rows, cols, t_sqrt.ref(), t_recip.ref(),
+                                    out_inv_scale, _p(q), _p(y), _p(s1), _p(s2)), "layernorm_pwl2")
+    return dict(y=y, q=q, seg_sqrt=s1, seg_recip=s2)
 
 
 def gemm_pwl(A, W, bias=None, alpha=1.0, alpha_vec=None, resid=None, resid_scale=0.0,

@@ -21,7 +21,7 @@ NM_DT_I32, NM_DT_F32 = 0, 1
 # every symbol include/nm.h declares
 EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_tables",
            "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_destroy",
-           "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_pwl_apply", "nm_attn_scores",
+           "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_layernorm_pwl2", "nm_pwl_apply", "nm_attn_scores",
            "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer",
            "nm_encoder_stack_workspace", "nm_encoder_stack", "nm_conv2d_workspace", "nm_conv2d_pwl",
            "nm_maxpool_i8", "nm_avgpool_i8")
@@ -114,6 +114,9 @@ def load(preload_torch: bool = True) -> C.CDLL:
     L.nm_layernorm_pwl.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int64,
                                    C.c_int32, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p]
+    L.nm_layernorm_pwl2.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_int64,
+                                    C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.nm_pwl_apply.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int64, C.c_void_p, C.c_int32,
                                C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.nm_attn_scores.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -278,6 +281,14 @@ def nm_layernorm_pwl(x, gamma, beta, eps, tables: Tables, rsqrt_idx, out_inv_sca
     _check(load().nm_layernorm_pwl(_ptr(x), _ptr(gamma), _ptr(beta), eps, rows, cols,
                                    tables.handle, rsqrt_idx, out_inv_scale, _ptr(out_q),
                                    _ptr(out_f32), _ptr(dbg_seg), _stream(stream)))
+
+
+def nm_layernorm_pwl2(x, gamma, beta, eps, tables: Tables, sqrt_idx, recip_idx, out_inv_scale, *,
+                      out_q=None, out_f32=None, dbg_seg_sqrt=None, dbg_seg_recip=None, stream=None):
+    rows, cols = x.shape
+    _check(load().nm_layernorm_pwl2(_ptr(x), _ptr(gamma), _ptr(beta), eps, rows, cols, tables.handle,
+                                    sqrt_idx, recip_idx, out_inv_scale, _ptr(out_q), _ptr(out_f32),
+                                    _ptr(dbg_seg_sqrt), _ptr(dbg_seg_recip), _stream(stream)))
 
 
 def nm_pwl_apply(x, alpha, tables: Tables, idx, out_inv_scale, *, out_q=None, out_f32=None,

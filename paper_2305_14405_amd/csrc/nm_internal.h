@@ -28,6 +28,11 @@ struct HostTable {
     size_t blob_offset;  // in float2 units
 };
 
+int32_t launch_layernorm2(const float* in, const float* gamma, const float* beta, float eps,
+                          int64_t rows, int32_t cols, const DevTable& t, const DevTable& t2, int two,
+                          float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* seg, uint16_t* seg2,
+                          hipStream_t stream);
+
 }  // namespace nm
 
 struct nm_tables {
@@ -88,5 +93,10 @@ int32_t launch_softmax(const void* in, int32_t in_dtype, float alpha, int64_t ro
 int32_t launch_layernorm(const float* in, const float* gamma, const float* beta, float eps,
                          int64_t rows, int32_t cols, const DevTable& t, float out_inv_scale,
                          int8_t* out_q, float* out_f32, uint16_t* seg, hipStream_t stream);
+
+int32_t launch_layernorm2(const float* in, const float* gamma, const float* beta, float eps,
+                          int64_t rows, int32_t cols, const DevTable& t, const DevTable& t2, int two,
+                          float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* seg, uint16_t* seg2,
+                          hipStream_t stream);
 
 }  // namespace nm

@@ -277,8 +277,9 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
 template <int G, int C, bool kVec, bool kFull>
 __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
     const float* __restrict__ in, const float* __restrict__ gamma, const float* __restrict__ beta,
-    float eps, float inv_L, long rows, int cols, DevTable t, float out_inv_scale,
-    int8_t* __restrict__ out_q, float* __restrict__ out_f32, uint16_t* __restrict__ seg)
+    float eps, float inv_L, long rows, int cols, DevTable t, DevTable t2, int two_tables,
+    float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
+    uint16_t* __restrict__ seg, uint16_t* __restrict__ seg2)
 {
     constexpr int kRowsPerWave = 64 / G;
     constexpr int kRowsPerBlock = kRowsPerWave * (kRowThreads / 64);
@@ -325,6 +326,7 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
         }
         if (!staged) {
             stage_table(s_kb, t);
+            if (two_tables) stage_table(s_kb + t.nseg, t2);
             __syncthreads();
             staged = true;
         }
@@ -341,8 +343,13 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_pwl_kernel(
         const float var = group_sum<G>(part2) * inv_L;
         const float u = var + eps;
         int sr;
-        const float r = pwl_eval(u, t, s_kb, sr);
+        float r = pwl_eval(u, t, s_kb, sr);   // rsqrt table, or the sqrt table of the two-table form
         if (seg && live && g == 0) seg[row] = (uint16_t)sr;
+        if (two_tables) {                      // ... followed by the reciprocal table
+            int sr2;
+            r = pwl_eval(r, t2, s_kb + t.nseg, sr2);
+            if (seg2 && live && g == 0) seg2[row] = (uint16_t)sr2;
+        }
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             const int j0 = 4 * (g + G * c);
@@ -451,19 +458,21 @@ int32_t launch_softmax(const void* in, int32_t in_dtype, float alpha, int64_t ro
 template <bool kVec>
 static bool launch_layernorm_t(RowShape rs, hipStream_t stream, const float* in, const float* gamma,
                                const float* beta, float eps, float inv_L, long rows, int cols,
-                               const DevTable& t, float ois, int8_t* oq, float* of, uint16_t* seg)
+                               const DevTable& t, const DevTable& t2, int two, float ois, int8_t* oq, float* of,
+                               uint16_t* seg, uint16_t* seg2)
 {
+    const size_t shmem = sizeof(float2) * ((size_t)t.nseg + (two ? (size_t)t2.nseg : 0));
 #define NM_LN_CASE(GG, CC)                                                                          \
     if (rs.G == GG && rs.C == CC) {                                                                 \
         constexpr int rpb = (64 / GG) * (kRowThreads / 64);                                         \
         if (kVec && cols == 4 * GG * CC)                                                            \
             hipLaunchKernelGGL((layernorm_pwl_kernel<GG, CC, kVec, kVec>), dim3(blocks_for(rows, rpb)), \
-                               dim3(kRowThreads), sizeof(float2) * (size_t)t.nseg, stream, in, gamma, \
-                               beta, eps, inv_L, rows, cols, t, ois, oq, of, seg);                  \
+                               dim3(kRowThreads), shmem, stream, in, gamma,                         \
+                               beta, eps, inv_L, rows, cols, t, t2, two, ois, oq, of, seg, seg2);   \
         else                                                                                        \
             hipLaunchKernelGGL((layernorm_pwl_kernel<GG, CC, kVec, false>), dim3(blocks_for(rows, rpb)), \
-                               dim3(kRowThreads), sizeof(float2) * (size_t)t.nseg, stream, in, gamma, \
-                               beta, eps, inv_L, rows, cols, t, ois, oq, of, seg);                  \
+                               dim3(kRowThreads), shmem, stream, in, gamma,                         \
+                               beta, eps, inv_L, rows, cols, t, t2, two, ois, oq, of, seg, seg2);   \
         return true;                                                                                \
     }
     NM_LN_CASE(1, 1) NM_LN_CASE(2, 1) NM_LN_CASE(4, 1) NM_LN_CASE(8, 1) NM_LN_CASE(16, 1)
@@ -477,14 +486,23 @@ int32_t launch_layernorm(const float* in, const float* gamma, const float* beta,
                          int64_t rows, int32_t cols, const DevTable& t, float out_inv_scale,
                          int8_t* out_q, float* out_f32, uint16_t* seg, hipStream_t stream)
 {
+    return launch_layernorm2(in, gamma, beta, eps, rows, cols, t, t, 0, out_inv_scale, out_q, out_f32, seg,
+                             nullptr, stream);
+}
+
+int32_t launch_layernorm2(const float* in, const float* gamma, const float* beta, float eps,
+                          int64_t rows, int32_t cols, const DevTable& t, const DevTable& t2, int two,
+                          float out_inv_scale, int8_t* out_q, float* out_f32, uint16_t* seg, uint16_t* seg2,
+                          hipStream_t stream)
+{
     if (rows == 0) return NM_OK;
     RowShape rs = row_shape(cols);
     if (rs.C < 0) return fail(NM_ERR_UNSUPPORTED, "layernorm: cols %d not supported", cols);
     const float inv_L = (float)(1.0 / (double)cols);
     const bool vec = cols % 4 == 0 && aligned(in, 16) && aligned(gamma, 16) && aligned(beta, 16) &&
                      (!out_f32 || aligned(out_f32, 16)) && (!out_q || aligned(out_q, 4));
-    bool ok = vec ? launch_layernorm_t<true>(rs, stream, in, gamma, beta, eps, inv_L, rows, cols, t, out_inv_scale, out_q, out_f32, seg)
-                  : launch_layernorm_t<false>(rs, stream, in, gamma, beta, eps, inv_L, rows, cols, t, out_inv_scale, out_q, out_f32, seg);
+    bool ok = vec ? launch_layernorm_t<true>(rs, stream, in, gamma, beta, eps, inv_L, rows, cols, t, t2, two, out_inv_scale, out_q, out_f32, seg, seg2)
+                  : launch_layernorm_t<false>(rs, stream, in, gamma, beta, eps, inv_L, rows, cols, t, t2, two, out_inv_scale, out_q, out_f32, seg, seg2);
     if (!ok) return fail(NM_ERR_UNSUPPORTED, "layernorm: no kernel for cols %d", cols);
     return check_hip(hipGetLastError(), "layernorm launch");
 }
@@ -561,6 +579,25 @@ int32_t nm_layernorm_pwl(const float* in, const float* gamma, const float* beta,
     if (!out_q && !out_f32) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl: no output");
     return launch_layernorm(in, gamma, beta, eps, rows, cols, t, out_inv_scale, out_q, out_f32,
                             dbg_seg, (hipStream_t)stream);
+}
+
+int32_t nm_layernorm_pwl2(const float* in, const float* gamma, const float* beta, float eps,
+                          int64_t rows, int32_t cols, const nm_tables* tables, int32_t sqrt_idx,
+                          int32_t recip_idx, float out_inv_scale, int8_t* out_q, float* out_f32,
+                          uint16_t* dbg_seg_sqrt, uint16_t* dbg_seg_recip, void* stream)
+{
+    if (rows < 0 || cols < 1) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl2: bad shape");
+    if (cols > 4096) return fail(NM_ERR_UNSUPPORTED, "nm_layernorm_pwl2: cols %d > 4096", cols);
+    if (!gamma || !beta) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl2: gamma or beta is NULL");
+    DevTable t, t2;
+    int32_t rc = get_dev_table(tables, sqrt_idx, &t, "nm_layernorm_pwl2(sqrt)");
+    if (rc) return rc;
+    if ((rc = get_dev_table(tables, recip_idx, &t2, "nm_layernorm_pwl2(recip)"))) return rc;
+    if (rows == 0) return NM_OK;
+    if (!in) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl2: in is NULL");
+    if (!out_q && !out_f32) return fail(NM_ERR_INVALID_ARG, "nm_layernorm_pwl2: no output");
+    return launch_layernorm2(in, gamma, beta, eps, rows, cols, t, t2, 1, out_inv_scale, out_q, out_f32,
+                             dbg_seg_sqrt, dbg_seg_recip, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -181,6 +181,30 @@ def test_layernorm_pwl(oracle, rows, cols):
     assert_f32_close(host(of), r["y"], f"layernorm fp32 {rows}x{cols}")
 
 
+@pytest.mark.parametrize("rows,cols", [(37, 96), (101, 128), (64, 768), (9, 1000), (5, 4096)])
+def test_layernorm_pwl2_sqrt_then_reciprocal(oracle, rows, cols):
+    """The two-table LayerNorm (square root, then reciprocal): segments of both tables, fp32 and
+    int8 outputs against the oracle."""
+    ot, dt = both_tables(oracle, [("sqrt", 0.0, 16.0, 128), ("recip", 0.25, 4.0, 64)])
+    x = W.float_rows(rows, cols, seed=rows + cols, std=1.4)
+    g = np.random.default_rng(cols)
+    gamma = (1 + 0.1 * g.standard_normal(cols)).astype(np.float32)
+    beta = (0.1 * g.standard_normal(cols)).astype(np.float32)
+    r = oracle.layernorm_pwl2(x, gamma, beta, 1e-5, ot[0], ot[1], 31.0)
+    oq = torch.empty((rows, cols), dtype=torch.int8, device=DEV)
+    of = torch.empty((rows, cols), dtype=torch.float32, device=DEV)
+    s1 = torch.empty(rows, dtype=torch.int16, device=DEV)
+    s2 = torch.empty(rows, dtype=torch.int16, device=DEV)
+    dx, dg, db = dev(x), dev(gamma), dev(beta)
+    nm.nm_layernorm_pwl2(dx, dg, db, 1e-5, dt, 0, 1, 31.0, out_q=oq, out_f32=of, dbg_seg_sqrt=s1,
+                         dbg_seg_recip=s2)
+    assert_exact(host(s1).view(np.uint16), r["seg_sqrt"], "sqrt segments")
+    assert_exact(host(s2).view(np.uint16), r["seg_recip"], "reciprocal segments")
+    assert_f32_close(host(of), r["y"], f"layernorm2 fp32 {rows}x{cols}")
+    assert_exact(host(oq), r["q"], "layernorm2 int8")
+    assert len(np.unique(r["seg_sqrt"])) > 2
+
+
 def test_layernorm_pwl_headline_shape(oracle):
     rows, cols = 4096, 768
     ot, dt = both_tables(oracle, [("rsqrt", 1e-3, 64.0, 128)])

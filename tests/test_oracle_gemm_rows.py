@@ -224,3 +224,63 @@ def test_layernorm_close_to_library_layer_norm(oracle):
         assert np.all(np.abs(r["y"][i] - ref[i]) <= bound), i
     want_q = np.clip(np.rint((r["y"] * np.float32(30.0)).astype(np.float32)), -127, 127)
     assert np.array_equal(r["q"].astype(np.float32), want_q)
+
+
+# ---- LayerNorm with a square-root table followed by a reciprocal table ----------------------------
+
+def test_layernorm2_break_points_are_exact(oracle):
+    """Row of +-2: variance 4.  sqrt table with break points at k/2 ... contains 4 -> sd = 2 exactly;
+    reciprocal table with break points at 1 + k/4 contains 2 -> r = 0.5 exactly; y = +-1."""
+    ts = oracle.build_table(oracle.F_SQRT, 0.0, 16.0, 32)
+    tr = oracle.build_table(oracle.F_RECIP, 1.0, 5.0, 16)
+    cols = 256
+    x = np.tile(np.array([2.0, -2.0], np.float32), cols // 2)[None, :]
+    r = oracle.layernorm_pwl2(x, np.ones(cols, np.float32), np.zeros(cols, np.float32), 0.0, ts, tr, 1.0)
+    assert r["seg_sqrt"][0] == 8 and r["seg_recip"][0] == 4
+    assert np.allclose(np.abs(r["y"]), 1.0, rtol=1e-6, atol=0)
+    assert np.array_equal(np.sign(r["y"]), np.sign(x))
+
+
+def test_layernorm2_is_the_composition_of_the_two_tables(oracle):
+    """r = PWL_recip(PWL_sqrt(var + eps)) with the same mean / variance as the one-table form: the
+    two forms differ only in r, so y2 - beta = (y1 - beta) * r2 / r1 up to one rounding each."""
+    cols = 200
+    x = W.float_rows(9, cols, seed=3, std=1.3)
+    gamma = np.ones(cols, np.float32)
+    beta = np.zeros(cols, np.float32)
+    t1 = oracle.build_table(oracle.F_RSQRT, 0.05, 16.0, 4096)
+    ts = oracle.build_table(oracle.F_SQRT, 0.05, 16.0, 4096)
+    tr = oracle.build_table(oracle.F_RECIP, 0.2, 4.0, 4096)
+    a = oracle.layernorm_pwl(x, gamma, beta, 1e-5, t1, 10.0)
+    b = oracle.layernorm_pwl2(x, gamma, beta, 1e-5, ts, tr, 10.0)
+    var = x.astype(np.float64).var(axis=1) + 1e-5
+    inside = (var > 0.1) & (var < 15.0)   # the generator also makes constant and extreme rows
+    assert inside.sum() >= 4
+    for i in np.nonzero(inside)[0]:
+        u = np.float32(var[i])
+        r2 = oracle.pwl_eval(float(oracle.pwl_eval(float(u), ts)), tr)
+        assert abs(float(r2) - var[i] ** -0.5) < 1e-4 * var[i] ** -0.5
+    live = (np.abs(a["y"]) > 1e-3) & inside[:, None]
+    assert np.allclose(b["y"][live], a["y"][live], rtol=2e-4)
+
+
+def test_layernorm2_close_to_library_layer_norm(oracle):
+    cols = 768
+    x = W.float_rows(16, cols, seed=11, std=1.5)
+    g = np.random.default_rng(12)
+    gamma = (1 + 0.1 * g.standard_normal(cols)).astype(np.float32)
+    beta = (0.1 * g.standard_normal(cols)).astype(np.float32)
+    ts = oracle.build_table(oracle.F_SQRT, 0.0, 16.0, 1024)
+    tr = oracle.build_table(oracle.F_RECIP, 0.25, 4.0, 1024)
+    r = oracle.layernorm_pwl2(x, gamma, beta, 1e-5, ts, tr, 30.0)
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x.astype(np.float64)), (cols,),
+                                         torch.from_numpy(gamma.astype(np.float64)),
+                                         torch.from_numpy(beta.astype(np.float64)), 1e-5).numpy()
+    sd = np.sqrt(x.astype(np.float64).var(axis=1) + 1e-5)
+    ok = (sd > 0.3) & (sd < 3.9)   # rows whose standard deviation lies well inside both tables
+    assert ok.sum() >= 8
+    # chord errors: sqrt w^2/8 * |f''| = (1/64)^2/8 * sd^-3/4, recip (3.75/1024)^2/8 * 2/sd^3: relative ~1e-5
+    assert np.abs(r["y"][ok] - ref[ok]).max() < 2e-3
+    const = oracle.layernorm_pwl2(np.full((1, 64), 0.5, np.float32), np.ones(64, np.float32),
+                                  np.full(64, 0.25, np.float32), 1e-5, ts, tr, 1.0)
+    assert np.all(const["y"] == 0.25)   # constant row: d = 0 -> y = beta
