@@ -36,18 +36,18 @@ ATTN_OPS_PER_SCORE = 18.0
 
 # HBM-side traffic per launch at the bert_base_layer shapes, from two rocprofv3 --pmc runs of this
 # script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch).  A plain 64 MiB device copy in the same
-# runs read FETCH_SIZE = 32781 and WRITE_SIZE = 65536, so FETCH_SIZE is scaled by 65536 / 32781 and
+# runs read FETCH_SIZE = 32786 and WRITE_SIZE = 65536, so FETCH_SIZE is scaled by 65536 / 32786 and
 # WRITE_SIZE by 1.  Counters cannot be read from inside this process: these are recorded values,
 # refreshed when a kernel's memory behaviour changes.
-PMC_FETCH_SCALE = 65536.0 / 32781.0
+PMC_FETCH_SCALE = 65536.0 / 32785.6
 PMC_KIB = {  # kernel -> (FETCH_SIZE, WRITE_SIZE) as the counters read
-    "qkv_gemm": (8041.9, 9216.0),
-    "attention_fused": (9324.8, 5120.6),
-    "out_proj_gemm": (12178.7, 12288.6),   # counter average over out_proj and ffn2 (same kernel)
-    "ffn2_gemm": (12178.7, 12288.6),
-    "ffn1_gelu_gemm": (8678.6, 12288.0),
-    "layernorm_pwl": (6196.6, 3072.0),
-    "softmax_pwl": (12319.4, 6144.0),
+    "qkv_gemm": (8135.7, 9216.1),
+    "attention_fused": (4677.0, 5120.0),
+    "out_proj_gemm": (12173.2, 12295.4),   # counter average over out_proj and ffn2 (same kernel)
+    "ffn2_gemm": (12173.2, 12295.4),
+    "ffn1_gelu_gemm": (8619.8, 12288.0),
+    "layernorm_pwl": (6198.2, 3072.0),
+    "softmax_pwl": (12319.3, 6144.0),
 }
 
 
