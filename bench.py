@@ -197,11 +197,18 @@ def main():
          lambda: nm.nm_gemm_pwl(taps["ln1"], devw["W1"], bias=devw["b1"], alpha=p["alpha_1"],
                                 tables=tables, table_idx=0, out_inv_scale=p["inv_s_ffn1"],
                                 out_q=taps["ffn1"])),
+        # the same GEMM with pre-activations spread over the whole GELU table (the workload's own
+        # values touch only a few segments): shows what the LDS gather costs under bank conflicts
+        ("ffn1_gelu_gemm_stress", "mfma", 2.0 * M * F * H,
+         lambda: nm.nm_gemm_pwl(taps["ln1"], devw["W1"], bias=devw["b1"], alpha=p["alpha_1"] * 12.0,
+                                tables=tables, table_idx=0, out_inv_scale=p["inv_s_ffn1"] / 12.0,
+                                out_q=stress_out)),
         ("ffn2_gemm", "mfma", 2.0 * M * H * F,
          lambda: nm.nm_gemm_pwl(taps["ffn1"], devw["W2"], bias=devw["b2"], alpha=p["alpha_2"],
                                 resid=taps["ln1"], resid_scale=p["resid2_scale"],
                                 out_f32=taps["ffn2"])),
     ]
+    stress_out = torch.empty((M, F), dtype=torch.int8, device=dev)
     kernels = []
     for name, bound, work, fn in stages:
         ms = timed(fn, args.kernel_reps)
@@ -240,21 +247,22 @@ def main():
     # stand-alone softmax row kernel is timed for its bandwidth figure only)
     fused_attn = H // nh == 64 and S <= 512 and H % 16 == 0
     for k in kernels:
-        k["in_layer"] = k["kernel"] != ("softmax_pwl" if fused_attn else "attention_fused")
+        k["in_layer"] = k["kernel"] not in (("softmax_pwl" if fused_attn else "attention_fused"),
+                                            "ffn1_gelu_gemm_stress")
     dom = max((k for k in kernels if k["in_layer"]), key=lambda k: k["ms"])
     roofline = dict(bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"], unit=dom["unit"],
                     frac=dom["frac"], traffic=dom["traffic"], kernel=dom["kernel"],
                     note="int8 MFMA rate in TOP/s (2 ops per multiply-accumulate)" if dom["bound"] == "mfma"
                     else "plain vector ALU, 18 scalar operations per attention score")
     gemm_ops = sum(2.0 * M * n * k for n, k in ((3 * H, H), (H, H), (F, H), (H, F)))
-    gemm_ms = sum(k["ms"] for k in kernels if k["bound"] == "mfma")
+    gemm_ms = sum(k["ms"] for k in kernels if k["bound"] == "mfma" and k["in_layer"])
     row_bytes = float(B * nh * S * S * 5 + 2 * M * H * 5)
     ln_ms = next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl")
     row_ms = next(k["ms"] for k in kernels if k["kernel"] == "softmax_pwl") + 2 * ln_ms
     summary = dict(int8_mfma_util_pct=round(100 * gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
                    nonlinear_hbm_gbs=round(row_bytes / (row_ms * 1e-3) / 1e9, 1),
                    nonlinear_hbm_gbs_large=round(sum(k["achieved"] for k in big) / len(big), 1),
-                   sum_kernel_ms=round(sum(k["ms"] for k in kernels if k["kernel"] != "softmax_pwl") + ln_ms, 4),
+                   sum_kernel_ms=round(sum(k["ms"] for k in kernels if k["in_layer"]) + ln_ms, 4),
                    note="softmax_pwl is the stand-alone row kernel (timed on its own; the layer uses the "
                         "fused attention kernel at this shape); layernorm_pwl runs twice per layer")
 
