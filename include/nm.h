@@ -178,7 +178,7 @@ int32_t nm_gemm_pwl(const nm_gemm_desc* desc, void* stream);
  * Outputs (device, any may be NULL, at least one of out_q / out_f32 required): out_q int8 codes
  * of p with out_inv_scale, out_f32 p, dbg_seg_exp [rows, cols] exp segment of every element,
  * dbg_seg_recip [rows] reciprocal segment of every row.
- * Limits: 1 <= cols <= 4096, rows >= 0, rows * cols < 2^40.
+ * Limits: 1 <= cols <= 4096, rows >= 0, rows * cols < 2^40; alpha finite (NM_ERR_INVALID_ARG).
  * --------------------------------------------------------------------------------------------- */
 int32_t nm_softmax_pwl(const void* in, int32_t in_dtype, float alpha, int64_t rows, int32_t cols,
                        const nm_tables* tables, int32_t exp_idx, int32_t recip_idx,
@@ -240,7 +240,8 @@ int32_t nm_attn_context(const int8_t* p, const int8_t* qkv, int32_t B, int32_t S
  * and the int8 probabilities stay in registers.  scores_out / p_out (device, [B,heads,S,S]) may be
  * NULL; when given they receive the intermediate tensors.
  * Limits: head size H / heads == 64, S <= 512, qkv 16-byte aligned, H % 16 == 0; other shapes
- * return NM_ERR_UNSUPPORTED and the caller uses the three separate calls.
+ * return NM_ERR_UNSUPPORTED and the caller uses the three separate calls.  alpha_scores must be
+ * finite (NM_ERR_INVALID_ARG otherwise).
  * --------------------------------------------------------------------------------------------- */
 int32_t nm_attention_pwl(const int8_t* qkv, int32_t B, int32_t S, int32_t H, int32_t heads,
                          float alpha_scores, const nm_tables* tables, int32_t exp_idx,

@@ -41,12 +41,18 @@ __device__ __forceinline__ float pwl_eval(float x, const DevTable& t, const floa
 // clamp flag is folded into the bounds (clo, chi = lo, hi with the flag, -inf, +inf without), so no
 // select is needed; identical results for every non-NaN x.
 __device__ __forceinline__ float pwl_eval_bounded(float x, float clo, float chi, const DevTable& t,
-                                                  const float2* kb)
+                                                  const float2* kb, int& seg)
 {
     x = __builtin_amdgcn_fmed3f(x, clo, chi);
-    const int seg = seg_index(x, t.lo, t.inv_w, t.nseg);
+    seg = seg_index(x, t.lo, t.inv_w, t.nseg);
     const float2 e = kb[seg];
     return __builtin_fmaf(e.x, x, e.y);
+}
+__device__ __forceinline__ float pwl_eval_bounded(float x, float clo, float chi, const DevTable& t,
+                                                  const float2* kb)
+{
+    int seg;
+    return pwl_eval_bounded(x, clo, chi, t, kb, seg);
 }
 
 // Without the clamp flag.

@@ -171,6 +171,8 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
     const int lane = threadIdx.x & 63;
     const int g = lane % G;
     const int sub = (threadIdx.x >> 6) * kRowsPerWave + lane / G;
+    const float clo = t_exp.clamp_input ? t_exp.lo : -__builtin_inff();
+    const float chi = t_exp.clamp_input ? t_exp.hi : __builtin_inff();
 
     for (long row0 = (long)blockIdx.x * kRowsPerBlock; row0 < rows;
          row0 += (long)gridDim.x * kRowsPerBlock) {
@@ -226,7 +228,9 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
             for (int q = 0; q < 4; ++q) {
                 if (ok[c][q]) {
                     float tt = kI32 ? (float)(ai[c][q] - mi) * alpha : (e[c][q] - mf) * alpha;
-                    e[c][q] = pwl_eval(tt, t_exp, s_kb, se[c][q]);
+                    // int32 scores times a finite alpha cannot be NaN: the clamp flag folds into the bounds
+                    e[c][q] = kI32 ? pwl_eval_bounded(tt, clo, chi, t_exp, s_kb, se[c][q])
+                                   : pwl_eval(tt, t_exp, s_kb, se[c][q]);
                     part = part + e[c][q];
                 } else {
                     e[c][q] = 0.0f;
@@ -549,6 +553,7 @@ int32_t nm_softmax_pwl(const void* in, int32_t in_dtype, float alpha, int64_t ro
     if (in_dtype != NM_DT_I32 && in_dtype != NM_DT_F32)
         return fail(NM_ERR_INVALID_ARG, "nm_softmax_pwl: bad in_dtype %d", in_dtype);
     if (rows < 0 || cols < 1) return fail(NM_ERR_INVALID_ARG, "nm_softmax_pwl: bad shape");
+    if (!(alpha == alpha) || __builtin_isinf(alpha)) return fail(NM_ERR_INVALID_ARG, "nm_softmax_pwl: alpha must be finite");
     if (cols > 4096) return fail(NM_ERR_UNSUPPORTED, "nm_softmax_pwl: cols %d > 4096", cols);
     if (rows > (1LL << 40) / cols) return fail(NM_ERR_UNSUPPORTED, "nm_softmax_pwl: too many elements");
     DevTable te, tr;
