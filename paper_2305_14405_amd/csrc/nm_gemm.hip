@@ -418,8 +418,19 @@ __device__ __forceinline__ int lds_off_bk(int row, int chunk)
 // (i, j) and channels c0.. a lane's 16 bytes are x[b, ho*stride - pad + i, wo*stride - pad + j,
 // c0 + 16*chunk ..] or, in the padding, 16 bytes of the zero line; only the per-lane source
 // address of the direct global -> LDS load changes, the rest of the kernel is the same.
+// Wavefronts per SIMD the register allocation should leave room for: as many workgroups per CU as
+// the operand ring lets LDS hold (small rings exist so that several workgroups overlap), at most 3.
+constexpr int stream_waves_per_simd(int ring_bytes, int waves)
+{
+    const int wgs = ring_bytes <= 49152 ? 3 : ring_bytes <= 73728 ? 2 : 1;
+    const int w = wgs * waves / 4;
+    return w < 1 ? 1 : w > 3 ? 3 : w;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int KSPLIT, int BK, int kStages, int kEpi, bool kConv = false>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT) void gemm_stream_kernel(GemmParams p)
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KSPLIT,
+                             stream_waves_per_simd(kStages * (BM + BN) * BK, WAVES_M * WAVES_N * KSPLIT))
+void gemm_stream_kernel(GemmParams p)
 {
     constexpr int NWT = WAVES_M * WAVES_N;       // wavefront tiles per workgroup
     constexpr int NW = NWT * KSPLIT;             // wavefronts per workgroup
