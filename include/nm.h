@@ -345,8 +345,9 @@ int32_t nm_encoder_stack(const nm_layer_desc* descs, int32_t n_layers, const int
  * NULL.  Outputs (device, any may be NULL, at least one required): out_q int8, out_f32, dbg_acc
  * int32, each [B, Ho, Wo, Cout].
  * Workspace: needed only when Cin is not a multiple of 64 (or x / w are not 16-byte aligned) and
- * the convolution is not 1x1 / stride 1 / no padding; query nm_conv2d_workspace (0 otherwise; ws
- * may then be NULL).  256-byte aligned, contents are scratch.  Nothing is allocated, the host
+ * the convolution is not 1x1 / stride 1 / no padding (a patch matrix, or for images of at most
+ * four channels a few KB for the repacked filter); query nm_conv2d_workspace (0 otherwise; ws may
+ * then be NULL).  256-byte aligned, contents are scratch.  Nothing is allocated, the host
  * does not wait.  Limits: kh*kw*Cin <= 65536, B*Ho*Wo < 2^31, B*Ho*Wo*Cout < 2^31.
  * --------------------------------------------------------------------------------------------- */
 typedef struct {

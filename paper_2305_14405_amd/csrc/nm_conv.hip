@@ -50,7 +50,39 @@ __global__ __launch_bounds__(kConvThreads) void im2col_kernel(
 }
 
 // Max pooling on int8 codes (exact, order-free); padding never takes part.  One thread per
-// output position and group of four channels (C % 4 == 0) or per single channel.
+// output position and 16 channels (C % 16 == 0, 16-byte loads).
+__global__ __launch_bounds__(kConvThreads) void maxpool16_kernel(
+    const int8_t* __restrict__ x, int H, int W, int C, int k, int stride, int pad, int Ho, int Wo,
+    long total, int8_t* __restrict__ y)
+{
+    const int cg = C / 16;
+    for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
+        const int c = (int)(idx % cg);
+        const long m = idx / cg;
+        const int wo = (int)(m % Wo), ho = (int)((m / Wo) % Ho);
+        const long b = m / ((long)Wo * Ho);
+        int best[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) best[e] = -128;
+        for (int i = 0; i < k; ++i) {
+            const int hi = ho * stride - pad + i;
+            if ((unsigned)hi >= (unsigned)H) continue;
+            for (int j = 0; j < k; ++j) {
+                const int wi = wo * stride - pad + j;
+                if ((unsigned)wi >= (unsigned)W) continue;
+                const v4i w4 = *reinterpret_cast<const v4i*>(x + ((b * H + hi) * W + wi) * C + 16 * c);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) best[e] = max(best[e], (int)(int8_t)((unsigned)w4[e >> 2] >> (8 * (e & 3))));
+            }
+        }
+        v4i o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o[q] = (int)pack4(best[4 * q], best[4 * q + 1], best[4 * q + 2], best[4 * q + 3]);
+        *reinterpret_cast<v4i*>(y + m * C + 16 * c) = o;
+    }
+}
+
+// The same with four channels (C % 4 == 0) or one channel per thread.
 template <bool kVec>
 __global__ __launch_bounds__(kConvThreads) void maxpool_kernel(
     const int8_t* __restrict__ x, int H, int W, int C, int k, int stride, int pad, int Ho, int Wo,
@@ -114,7 +146,7 @@ __global__ __launch_bounds__(kConvThreads) void avgpool_kernel(
 // A wavefront owns 4 rows x 16 columns of positions and all (up to 64) output channels.
 // ---------------------------------------------------------------------------------------------
 struct StemParams {
-    const int8_t* x; const int8_t* w;
+    const int8_t* x; const int8_t* w;   // w: the packed filter [64][kh][32] (stem_pack_filter_kernel)
     const float* bias; const float* alpha_vec;
     float alpha, out_inv_scale;
     int has_table;
@@ -123,6 +155,22 @@ struct StemParams {
     int prow, pcol, pitch;   // staged image patch: rows, pixels per row, bytes per row
     int8_t* out_q;
 };
+
+// Packs the filter [Cout][kh][kw][Cin] into [64][kh][8 pixels of 4 bytes] (zero filled), once per
+// call, so that every workgroup of the convolution copies it with wide loads.
+__global__ __launch_bounds__(256) void stem_pack_filter_kernel(const int8_t* __restrict__ w, int Cout, int kh,
+                                                               int kw, int Cin, int8_t* __restrict__ out)
+{
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < 64 * kh * 8; idx += gridDim.x * blockDim.x) {
+        const int j = idx % 8, i = (idx / 8) % kh, n = idx / (8 * kh);
+        unsigned px = 0;
+        if (n < Cout && j < kw) {
+            const int8_t* src = w + (((long)n * kh + i) * kw + j) * Cin;
+            for (int ch = 0; ch < Cin; ++ch) px |= (unsigned)(uint8_t)src[ch] << (8 * ch);
+        }
+        *reinterpret_cast<unsigned*>(out + (n * kh + i) * 32 + 4 * j) = px;
+    }
+}
 
 __global__ __launch_bounds__(256) void stem_conv_kernel(StemParams p)
 {
@@ -160,16 +208,9 @@ __global__ __launch_bounds__(256) void stem_conv_kernel(StemParams p)
         const int per = (p.pitch - 4 * p.pcol) / 4;
         *reinterpret_cast<unsigned*>(sX + (idx / per) * p.pitch + 4 * p.pcol + 4 * (idx % per)) = 0u;
     }
-    // filter: [n][i][8 pixels of 4 bytes]
-    for (int idx = tid; idx < 64 * p.kh * 8; idx += 256) {
-        const int j = idx % 8, i = (idx / 8) % p.kh, n = idx / (8 * p.kh);
-        unsigned px = 0;
-        if (n < p.Cout && j < p.kw) {
-            const int8_t* src = p.w + (((long)n * p.kh + i) * p.kw + j) * p.Cin;
-            for (int ch = 0; ch < p.Cin; ++ch) px |= (unsigned)(uint8_t)src[ch] << (8 * ch);
-        }
-        *reinterpret_cast<unsigned*>(sW + (n * p.kh + i) * 32 + 4 * j) = px;
-    }
+    // filter, already packed as [n][i][8 pixels of 4 bytes]: straight 16-byte copies
+    for (int idx = tid; idx < 64 * p.kh * 2; idx += 256)
+        *reinterpret_cast<v4i*>(sW + 16 * idx) = *reinterpret_cast<const v4i*>(p.w + 16 * idx);
     __syncthreads();
 
     // lane (m, half): position m of a 32-position block; block t covers wavefront rows 2t, 2t+1
@@ -279,7 +320,8 @@ static int32_t plan_conv(const nm_conv_desc* d, const char* what, ConvPlan* pl)
                         !d->out_f32 && !d->dbg_acc && !d->resid && aligned(d->out_q, 16) &&
                         15 * d->stride + d->kh <= 64 && d->B <= 65535;
     pl->route = plain ? 0 : gather ? 1 : direct ? 3 : 2;
-    pl->ws_bytes = pl->route == 2 ? (size_t)M * pl->K16 + (size_t)d->Cout * pl->K16 : 0;
+    pl->ws_bytes = pl->route == 2 ? (size_t)M * pl->K16 + (size_t)d->Cout * pl->K16
+                 : pl->route == 3 ? (size_t)64 * d->kh * 32 : 0;   // patch matrix + filter rows | packed filter
     return NM_OK;
 }
 
@@ -333,8 +375,14 @@ int32_t nm_conv2d_pwl(const nm_conv_desc* d, void* ws, size_t ws_bytes, void* st
     g.ldo = d->Cout;
     g.out_q = d->out_q; g.out_f32 = d->out_f32; g.out_acc = d->dbg_acc;
     if (pl.route == 3) {
+        if (!ws) return fail(NM_ERR_WORKSPACE, "nm_conv2d_pwl: workspace is NULL");
+        if (!aligned(ws, 256)) return fail(NM_ERR_WORKSPACE, "nm_conv2d_pwl: workspace not 256-byte aligned");
+        if (ws_bytes < pl.ws_bytes)
+            return fail(NM_ERR_WORKSPACE, "nm_conv2d_pwl: workspace %zu bytes < %zu needed", ws_bytes, pl.ws_bytes);
+        hipLaunchKernelGGL(stem_pack_filter_kernel, dim3((64 * d->kh * 8 + 255) / 256), dim3(256), 0, stream, d->w,
+                           d->Cout, d->kh, d->kw, d->Cin, static_cast<int8_t*>(ws));
         StemParams sp{};
-        sp.x = d->x; sp.w = d->w; sp.bias = d->bias; sp.alpha_vec = d->alpha_vec; sp.alpha = d->alpha;
+        sp.x = d->x; sp.w = static_cast<const int8_t*>(ws); sp.bias = d->bias; sp.alpha_vec = d->alpha_vec; sp.alpha = d->alpha;
         sp.out_inv_scale = d->out_inv_scale; sp.has_table = g.has_table; sp.table = g.table;
         sp.B = d->B; sp.H = d->H; sp.W = d->W; sp.Cin = d->Cin; sp.Cout = d->Cout; sp.kh = d->kh; sp.kw = d->kw;
         sp.stride = d->stride; sp.pad = d->pad; sp.Ho = pl.Ho; sp.Wo = pl.Wo;
@@ -391,6 +439,12 @@ int32_t nm_maxpool_i8(const int8_t* x, int32_t B, int32_t H, int32_t W, int32_t 
     if (rows == 0) return NM_OK;
     if (!x || !y) return fail(NM_ERR_INVALID_ARG, "nm_maxpool_i8: NULL pointer");
     const bool vec = C % 4 == 0 && aligned(x, 4) && aligned(y, 4);
+    if (C % 16 == 0 && aligned(x, 16) && aligned(y, 16)) {
+        const long total16 = rows * (C / 16);
+        hipLaunchKernelGGL(maxpool16_kernel, dim3(grid_for(total16)), dim3(kConvThreads), 0, (hipStream_t)stream,
+                           x, H, W, C, k, stride, pad, Ho, Wo, total16, y);
+        return check_hip(hipGetLastError(), "nm_maxpool_i8 launch");
+    }
     const long total = rows * (vec ? C / 4 : C);
     if (vec) hipLaunchKernelGGL(maxpool_kernel<true>, dim3(grid_for(total)), dim3(kConvThreads), 0, (hipStream_t)stream,
                                 x, H, W, C, k, stride, pad, Ho, Wo, total, y);
