@@ -887,15 +887,16 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     // fill the chip; several small workgroups per CU (MID2 / MID3: 128x128, 64-byte slices, two or
     // three stages, 32 / 48 KB of LDS) when there are at least three 128x128 tiles per CU, so that
     // one workgroup's epilogue overlaps another's loads; SPLIT (128x128, two wavefronts per
-    // sub-tile, 128-byte slices) when tiles are scarce; NARROW (256x64) for outputs of at most 64 columns.
+    // sub-tile, 128-byte slices) when tiles are scarce, SMALL (64x128, same scheme) when even those
+    // would leave more than a third of the CUs idle; NARROW (256x64) for outputs of at most 64 columns.
     const bool k128 = g.K % 128 == 0 && (!g.conv || g.cCin % 128 == 0);  // 128-byte k-slices fetch ~1.5x faster
     const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 191) / 192) * batches;
     const long mid_tiles = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * batches;
-    enum { CFG_BIG, CFG_SPLIT, CFG_MID3, CFG_MID2, CFG_NARROW } cfg;
+    enum { CFG_BIG, CFG_SPLIT, CFG_SMALL, CFG_MID3, CFG_MID2, CFG_NARROW } cfg;
     if (g.N <= 64) cfg = CFG_NARROW;
     else if (!g.conv && k128 && g.N >= 1536 && big_tiles >= 192 && !force_mid_tile()) cfg = CFG_BIG;
     else if (mid_tiles >= 768 && !force_mid_tile()) cfg = g.K <= 256 ? CFG_MID2 : CFG_MID3;
-    else if (k128 && table_bytes <= 32768) cfg = CFG_SPLIT;
+    else if (k128 && table_bytes <= 32768) cfg = (mid_tiles < 160 && g.M > 64) ? CFG_SMALL : CFG_SPLIT;
     else cfg = CFG_MID3;
     if (g.conv) {
         // gathered A operand: streaming kernel only (the caller has checked Cin % 64 == 0, 16-byte
@@ -905,6 +906,7 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         if (cfg == CFG_NARROW) rc = launch_stream_conv<256, 64, 4, 1, 1, 64, 2>(p, epi, table_bytes, stream);
         else if (cfg == CFG_MID2) rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 2>(p, epi, table_bytes, stream);
         else if (cfg == CFG_SPLIT) rc = launch_stream_conv<128, 128, 2, 2, 2, 128, 3>(p, epi, table_bytes, stream);
+        else if (cfg == CFG_SMALL) rc = launch_stream_conv<64, 128, 1, 2, 2, 128, 3>(p, epi, table_bytes, stream);
         else rc = launch_stream_conv<128, 128, 2, 2, 1, 64, 3>(p, epi, table_bytes, stream);
         if (rc) return rc;
         return check_hip(hipGetLastError(), "conv gemm launch");
@@ -914,6 +916,8 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         rc = launch_stream<256, 192, 4, 2, 1, 128, 2>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && cfg == CFG_MID2) {
         rc = launch_stream<128, 128, 2, 2, 1, 64, 2>(p, epi, batches, table_bytes, stream);
+    } else if (stream_ok && cfg == CFG_SMALL) {
+        rc = launch_stream<64, 128, 1, 2, 2, 128, 3>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && cfg == CFG_SPLIT) {
         rc = launch_stream<128, 128, 2, 2, 2, 128, 3>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && cfg == CFG_MID3) {
