@@ -406,9 +406,22 @@ def bench_resnet(args):
         else:
             nm.nm_gemm_pwl(a[0], a[1], bias=a[2], alpha=a[3], out_f32=a[4])
 
+    # the whole network as one C-ABI call (nm_cnn_run over the list of steps)
+    ops = []
+    for kind, _, a in calls:
+        if kind == "conv":
+            ops.append(nm.cnn_op_conv(a))
+        elif kind == "maxpool":
+            ops.append(nm.cnn_op_maxpool(a[0], a[1], a[2], a[3], a[4]))
+        elif kind == "avgpool":
+            ops.append(nm.cnn_op_avgpool(a[0], a[1], a[2], out_q=a[3]))
+        else:
+            ops.append(nm.cnn_op_gemm(nm.make_gemm_desc(a[0], a[1], bias=a[2], alpha=a[3], out_f32=a[4])))
+    assert nm.nm_cnn_workspace(ops) <= ws_need
+    op_array = nm._op_array(ops)
+
     def step():
-        for c in calls:
-            run(c)
+        nm.nm_cnn_run(ops, ws, op_array=op_array)
 
     for _ in range(args.warmup):
         step()

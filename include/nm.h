@@ -386,6 +386,32 @@ int32_t nm_maxpool_i8(const int8_t* x, int32_t B, int32_t H, int32_t W, int32_t 
 int32_t nm_avgpool_i8(const int8_t* x, int32_t B, int32_t HW, int32_t C, float alpha, float out_inv_scale,
                       int8_t* out_q, float* out_f32, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * nm_cnn_run: a list of convolution / pooling / matrix-product steps queued back to back on one
+ * stream (a whole residual CNN in one call; the steps are the entry points above, so results are
+ * identical to calling them one by one).  ops: HOST array, read during the call only; every tensor
+ * pointer inside is a device pointer owned by the caller, who also wires each step's input to an
+ * earlier step's output.  ws: one workspace shared by all steps (query nm_cnn_workspace: the
+ * largest any step needs).  Stops at the first failing step and returns its status.
+ * --------------------------------------------------------------------------------------------- */
+enum { NM_OP_CONV = 0, NM_OP_MAXPOOL = 1, NM_OP_AVGPOOL = 2, NM_OP_GEMM = 3 };
+
+typedef struct {
+    int32_t kind;                 /* NM_OP_* */
+    nm_conv_desc conv;            /* NM_OP_CONV */
+    nm_gemm_desc gemm;            /* NM_OP_GEMM */
+    /* NM_OP_MAXPOOL: x [B,H,W,C] -> y, window k, stride, pad.  NM_OP_AVGPOOL: x [B,HW,C] (H = HW,
+     * W unused), alpha, out_inv_scale -> y (int8) and / or y_f32. */
+    const int8_t* x;
+    int8_t* y;
+    float* y_f32;
+    int32_t B, H, W, C, k, stride, pad;
+    float alpha, out_inv_scale;
+} nm_cnn_op;
+
+int32_t nm_cnn_workspace(const nm_cnn_op* ops, int32_t n_ops, size_t* bytes);
+int32_t nm_cnn_run(const nm_cnn_op* ops, int32_t n_ops, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,8 @@ EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_table
            "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_layernorm_pwl2", "nm_pwl_apply", "nm_attn_scores",
            "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer",
            "nm_encoder_stack_workspace", "nm_encoder_stack", "nm_conv2d_workspace", "nm_conv2d_pwl",
-           "nm_maxpool_i8", "nm_avgpool_i8")
+           "nm_maxpool_i8", "nm_avgpool_i8", "nm_cnn_workspace", "nm_cnn_run")
+NM_OP_CONV, NM_OP_MAXPOOL, NM_OP_AVGPOOL, NM_OP_GEMM = 0, 1, 2, 3
 
 
 class NmError(RuntimeError):
@@ -53,6 +54,13 @@ class ConvDesc(C.Structure):
         ("alpha", C.c_float), ("resid", C.c_void_p), ("resid_scale", C.c_float),
         ("tables", C.c_void_p), ("table_idx", C.c_int32), ("out_inv_scale", C.c_float),
         ("out_q", C.c_void_p), ("out_f32", C.c_void_p), ("dbg_acc", C.c_void_p)]
+
+
+class CnnOp(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("conv", ConvDesc), ("gemm", GemmDesc), ("x", C.c_void_p),
+                ("y", C.c_void_p), ("y_f32", C.c_void_p)] + \
+               [(n, C.c_int32) for n in ("B", "H", "W", "C", "k", "stride", "pad")] + \
+               [("alpha", C.c_float), ("out_inv_scale", C.c_float)]
 
 
 LAYER_FLOATS = ("alpha_qkv", "inv_s_q", "inv_s_k", "inv_s_v", "alpha_scores", "inv_s_p",
@@ -134,6 +142,8 @@ def load(preload_torch: bool = True) -> C.CDLL:
     L.nm_maxpool_i8.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
     L.nm_avgpool_i8.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_float,
                                 C.c_void_p, C.c_void_p, C.c_void_p]
+    L.nm_cnn_workspace.argtypes = [C.POINTER(CnnOp), C.c_int32, C.POINTER(C.c_size_t)]
+    L.nm_cnn_run.argtypes = [C.POINTER(CnnOp), C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
     L.nm_encoder_stack_workspace.argtypes = [C.POINTER(LayerDesc), C.c_int32, C.POINTER(C.c_size_t)]
     L.nm_encoder_stack.argtypes = [C.POINTER(LayerDesc), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]
@@ -407,3 +417,66 @@ def nm_avgpool_i8(x, alpha, out_inv_scale, *, out_q=None, out_f32=None, stream=N
     B, HW, Cc = (int(v) for v in x.shape)
     _check(load().nm_avgpool_i8(_ptr(x), B, HW, Cc, alpha, out_inv_scale, _ptr(out_q), _ptr(out_f32),
                                 _stream(stream)))
+
+
+def make_gemm_desc(A, W, *, bias=None, alpha=1.0, alpha_vec=None, resid=None, resid_scale=0.0,
+                   tables: Tables | None = None, table_idx=-1, out_inv_scale=1.0, out_q=None, out_f32=None) -> GemmDesc:
+    d = GemmDesc()
+    d.M, d.K, d.N = int(A.shape[0]), int(A.shape[1]), int(W.shape[0])
+    d.A, d.W, d.bias, d.alpha_vec = _ptr(A), _ptr(W), _ptr(bias), _ptr(alpha_vec)
+    d.alpha = alpha
+    d.resid, d.resid_scale = _ptr(resid), resid_scale
+    d.tables = tables.handle if tables is not None else None
+    d.table_idx = table_idx
+    d.out_inv_scale = out_inv_scale
+    d.out_q, d.out_f32 = _ptr(out_q), _ptr(out_f32)
+    return d
+
+
+def cnn_op_conv(desc: ConvDesc) -> CnnOp:
+    o = CnnOp()
+    o.kind, o.conv = NM_OP_CONV, desc
+    return o
+
+
+def cnn_op_gemm(desc: GemmDesc) -> CnnOp:
+    o = CnnOp()
+    o.kind, o.gemm = NM_OP_GEMM, desc
+    return o
+
+
+def cnn_op_maxpool(x, y, k=3, stride=2, pad=1) -> CnnOp:
+    o = CnnOp()
+    o.kind, o.x, o.y = NM_OP_MAXPOOL, _ptr(x), _ptr(y)
+    o.B, o.H, o.W, o.C = (int(v) for v in x.shape)
+    o.k, o.stride, o.pad = k, stride, pad
+    return o
+
+
+def cnn_op_avgpool(x, alpha, out_inv_scale, out_q=None, out_f32=None) -> CnnOp:
+    """x [B, HW, C]."""
+    o = CnnOp()
+    o.kind, o.x, o.y, o.y_f32 = NM_OP_AVGPOOL, _ptr(x), _ptr(out_q), _ptr(out_f32)
+    o.B, o.H, o.C = (int(v) for v in x.shape)
+    o.alpha, o.out_inv_scale = alpha, out_inv_scale
+    return o
+
+
+def _op_array(ops):
+    arr = (CnnOp * len(ops))()
+    for i, o in enumerate(ops):
+        C.memmove(C.byref(arr, i * C.sizeof(CnnOp)), C.byref(o), C.sizeof(CnnOp))
+    return arr
+
+
+def nm_cnn_workspace(ops) -> int:
+    n = C.c_size_t()
+    _check(load().nm_cnn_workspace(_op_array(ops), len(ops), C.byref(n)))
+    return n.value
+
+
+def nm_cnn_run(ops, ws=None, stream=None, ws_bytes=None, op_array=None):
+    """ops: list of CnnOp (or pass a prebuilt ctypes array as op_array to skip the copy)."""
+    arr = op_array if op_array is not None else _op_array(ops)
+    nbytes = 0 if ws is None else (ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes)
+    _check(load().nm_cnn_run(arr, len(arr), _ptr(ws), nbytes, _stream(stream)))

@@ -466,4 +466,41 @@ int32_t nm_avgpool_i8(const int8_t* x, int32_t B, int32_t HW, int32_t C, float a
     return check_hip(hipGetLastError(), "nm_avgpool_i8 launch");
 }
 
+int32_t nm_cnn_workspace(const nm_cnn_op* ops, int32_t n_ops, size_t* bytes)
+{
+    if (!ops || n_ops < 1) return fail(NM_ERR_INVALID_ARG, "nm_cnn_workspace: no steps");
+    if (!bytes) return fail(NM_ERR_INVALID_ARG, "nm_cnn_workspace: bytes is NULL");
+    size_t need = 0;
+    for (int32_t i = 0; i < n_ops; ++i) {
+        if (ops[i].kind == NM_OP_CONV) {
+            size_t b = 0;
+            int32_t rc = nm_conv2d_workspace(&ops[i].conv, &b);
+            if (rc) return rc;
+            if (b > need) need = b;
+        } else if (ops[i].kind < NM_OP_CONV || ops[i].kind > NM_OP_GEMM) {
+            return fail(NM_ERR_INVALID_ARG, "nm_cnn_workspace: step %d has unknown kind %d", i, ops[i].kind);
+        }
+    }
+    *bytes = need;
+    return NM_OK;
+}
+
+int32_t nm_cnn_run(const nm_cnn_op* ops, int32_t n_ops, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!ops || n_ops < 1) return fail(NM_ERR_INVALID_ARG, "nm_cnn_run: no steps");
+    for (int32_t i = 0; i < n_ops; ++i) {
+        const nm_cnn_op& o = ops[i];
+        int32_t rc;
+        switch (o.kind) {
+        case NM_OP_CONV: rc = nm_conv2d_pwl(&o.conv, ws, ws_bytes, stream); break;
+        case NM_OP_MAXPOOL: rc = nm_maxpool_i8(o.x, o.B, o.H, o.W, o.C, o.k, o.stride, o.pad, o.y, stream); break;
+        case NM_OP_AVGPOOL: rc = nm_avgpool_i8(o.x, o.B, o.H, o.C, o.alpha, o.out_inv_scale, o.y, o.y_f32, stream); break;
+        case NM_OP_GEMM: rc = nm_gemm_pwl(&o.gemm, stream); break;
+        default: return fail(NM_ERR_INVALID_ARG, "nm_cnn_run: step %d has unknown kind %d", i, o.kind);
+        }
+        if (rc) return rc;
+    }
+    return NM_OK;
+}
+
 }  // extern "C"

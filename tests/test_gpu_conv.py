@@ -205,3 +205,47 @@ def test_resnet50_batch64_launch_configuration_sampled(oracle):
     assert np.array_equal(logits[:2].view(np.uint32), want["logits"].view(np.uint32))
     assert np.array_equal(logits[63], logits[0]) and np.array_equal(logits[37], logits[1])
     assert np.array_equal(host(got["tensors"]["s3b2c"])[63], host(got["tensors"]["s3b2c"])[0])
+
+
+def test_cnn_run_matches_oracle_network(oracle):
+    """nm_cnn_run (the whole network as one call over a list of steps) on resnet_tiny."""
+    p = W.resnet_params("resnet_tiny", 0)
+    ot, dt = relu_tables(oracle)
+    want = oracle.resnet_forward(p, keep=True)
+    B = p["B"]
+    cur = {"x": dev(p["x"])}
+    ops, keep = [], []
+    for op in p["graph"]:
+        n = op["name"]
+        if op["op"] == "conv":
+            y = torch.empty((B, op["Ho"], op["Ho"], op["Cout"]), dtype=torch.int8, device=DEV)
+            wt, bi, av = dev(p["w"][n]), dev(p["bias"][n]), dev(p["alpha_vec"][n])
+            keep += [wt, bi, av]
+            ops.append(nm.cnn_op_conv(nm.make_conv_desc(
+                cur[op["src"]], wt, op["stride"], op["pad"], bias=bi, alpha_vec=av,
+                resid=cur[op["resid"]] if op["resid"] else None, resid_scale=p["resid_scale"][n], tables=dt,
+                table_idx=0 if op["relu"] else -1, out_inv_scale=p["inv_s"][n], out_q=y)))
+            cur[op["dst"]] = y
+        elif op["op"] == "maxpool":
+            y = torch.empty((B, op["Ho"], op["Ho"], op["C"]), dtype=torch.int8, device=DEV)
+            ops.append(nm.cnn_op_maxpool(cur[op["src"]], y, op["k"], op["stride"], op["pad"]))
+            cur[op["dst"]] = y
+        elif op["op"] == "avgpool":
+            y = torch.empty((B, op["C"]), dtype=torch.int8, device=DEV)
+            ops.append(nm.cnn_op_avgpool(cur[op["src"]].view(B, -1, op["C"]), p["alpha"][n], p["inv_s"][n], out_q=y))
+            cur[op["dst"]] = y
+        else:
+            logits = torch.empty((B, op["Cout"]), dtype=torch.float32, device=DEV)
+            wt, bi = dev(p["w"][n]), dev(p["bias"][n])
+            keep += [wt, bi]
+            ops.append(nm.cnn_op_gemm(nm.make_gemm_desc(cur[op["src"]], wt, bias=bi, alpha=p["alpha"][n], out_f32=logits)))
+    ws = torch.empty(max(256, nm.nm_cnn_workspace(ops)), dtype=torch.uint8, device=DEV)
+    nm.nm_cnn_run(ops, ws)
+    for k, v in want["tensors"].items():
+        assert np.array_equal(host(cur[k]), v), f"nm_cnn_run: tensor {k}"
+    assert np.array_equal(host(logits).view(np.uint32), want["logits"].view(np.uint32))
+    bad = nm.CnnOp()
+    bad.kind = 9
+    with pytest.raises(nm.NmError) as ei:
+        nm.nm_cnn_run([bad], ws)
+    assert ei.value.status == nm.NM_ERR_INVALID_ARG
