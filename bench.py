@@ -430,7 +430,41 @@ def bench_resnet(args):
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_eager = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step, launch_mode = ms_eager, "eager"
+    # The 57 launches of a batch leave dispatch gaps; the same call recorded once into a HIP graph
+    # and replayed closes most of them.  Every replay is checked against the eager result (with
+    # eager work and synchronisation in between) before its timing is used.
+    eager_logits = logits.clone()
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        same = True
+        for _ in range(3):
+            logits.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            same = same and bool(torch.equal(logits, eager_logits))
+            step()
+            torch.cuda.synchronize()
+        if not same:
+            print("graph replay differs from the eager result: not used", file=sys.stderr)
+        if same:
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            ms_graph = (time.perf_counter() - t0) * 1e3 / args.steps
+            print(f"graph replay {ms_graph:.4f} ms vs eager {ms_eager:.4f} ms", file=sys.stderr)
+            if ms_graph < ms_per_step:
+                ms_per_step, launch_mode = ms_graph, "hip graph replay (checked against eager on 3 replays)"
+    except Exception as e:  # capture not available: keep the eager figure
+        launch_mode = f"eager (graph capture failed: {type(e).__name__})"
 
     kernels = []
     for c in calls:
@@ -479,7 +513,8 @@ def bench_resnet(args):
                warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="int8 (int32 accumulate, fp32 epilogue)", data="synthetic",
                config=dict(workload=args.workload, B=B, image=cfg["HW"], stages=list(cfg["stages"]),
-                           widths=list(cfg["widths"]), classes=cfg["classes"]),
+                           widths=list(cfg["widths"]), classes=cfg["classes"], launch=launch_mode,
+                           ms_per_step_eager=round(ms_eager, 5)),
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, summary=summary, parity=parity)
     print(json.dumps(out))
 
