@@ -1,5 +1,5 @@
 // Fused attention for gfx950: scores = Q K^T, softmax-PWL, context = P V in one kernel, per
-// (batch, head, block of 64 queries).  The int32 scores and the int8 probabilities never leave
+// (batch, head, block of 64 or 128 queries).  The int32 scores and the int8 probabilities never leave
 // registers (they are written out only when the caller asks for them).
 //
 // Paper basis: Section 3.1 (attention is a linear operation mapped to matrix products) and
@@ -38,7 +38,10 @@ struct AttnParams {
     int ctx_vec16;        // ctx is 16-byte aligned: context rows leave as 16-byte stores
 };
 
-constexpr int kAttnThreads = 256;   // four wavefronts, 64 queries
+// Wavefronts per workgroup: four (64 queries) up to 256 keys, where many small workgroups balance
+// best; eight (128 queries) beyond 256 keys, where the K / V staging per workgroup is large and is then
+// shared by twice as many queries.
+constexpr int attn_waves(int nkb) { return nkb >= 8 ? 8 : 4; }
 constexpr int kHeadDim = 64;
 
 // K image: 64-byte rows, the four 16-byte chunks of a row rotated by (row / 4) % 4 so that the 16
@@ -67,8 +70,10 @@ __device__ __forceinline__ void transpose4x4(const unsigned in[4], unsigned out[
 // NKB: padded key count / 64.  kFull: S == 64 * NKB, so no key or query is masked (removes every
 // per-key predicate).
 template <int NKB, bool kFull>
-__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2))) void attention_pwl_kernel(AttnParams p)
+__global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_per_eu(2))) void attention_pwl_kernel(AttnParams p)
 {
+    constexpr int kAttnThreads = 64 * attn_waves(NKB);
+    constexpr int kQueries = 16 * attn_waves(NKB);   // queries per workgroup
     constexpr int SK = NKB * 64;   // padded key count
     constexpr int NBLK = SK / 16;  // 16-key blocks
     constexpr int SV = SK + 16;    // row stride of the transposed V image
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(2)
         }
     }
     // this lane's query row, straight from global memory into the MFMA operand registers
-    const int m = bx * 64 + wave * 16 + fr;
+    const int m = bx * kQueries + wave * 16 + fr;
     v4i qf = {0, 0, 0, 0};
     if (kFull || m < S) qf = *reinterpret_cast<const v4i*>(base + (long)m * ld + 16 * hq);
     __syncthreads();
@@ -280,9 +285,10 @@ static int32_t launch_attention(const AttnParams& p, hipStream_t st)
         if (rc) return rc;
         configured = true;
     }
-    const dim3 grid((p.S + 63) / 64, p.B * p.heads);
-    if (p.S == 64 * NKB) hipLaunchKernelGGL((attention_pwl_kernel<NKB, true>), grid, dim3(kAttnThreads), shmem, st, p);
-    else hipLaunchKernelGGL((attention_pwl_kernel<NKB, false>), grid, dim3(kAttnThreads), shmem, st, p);
+    constexpr int kThreads = 64 * attn_waves(NKB), kQueries = 16 * attn_waves(NKB);
+    const dim3 grid((p.S + kQueries - 1) / kQueries, p.B * p.heads);
+    if (p.S == 64 * NKB) hipLaunchKernelGGL((attention_pwl_kernel<NKB, true>), grid, dim3(kThreads), shmem, st, p);
+    else hipLaunchKernelGGL((attention_pwl_kernel<NKB, false>), grid, dim3(kThreads), shmem, st, p);
     return NM_OK;
 }
 
