@@ -106,12 +106,22 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
     float2* s_kb_recip = s_kb + p.t_exp.nseg;
     stage_table(s_kb, p.t_exp);
     stage_table(s_kb_recip, p.t_recip);
-    // K tile -> LDS (rows past S are zero)
-    for (int idx = tid; idx < SK * 4; idx += kAttnThreads) {
-        const int r = idx >> 2, c = idx & 3;
-        v4i kv = {0, 0, 0, 0};
-        if (kFull || r < S) kv = *reinterpret_cast<const v4i*>(base + (long)r * ld + H + 16 * c);
-        *reinterpret_cast<v4i*>(&sK[attn_koff(r, c)]) = kv;
+    // K tile -> LDS.  With every row present the copy is a direct global -> LDS load (16 rows of
+    // 64 bytes per wavefront instruction; the chunk rotation is applied to the source address); it
+    // is in flight while V is transposed below.  Otherwise through registers, rows past S zero.
+    if (kFull) {
+        const unsigned lds_k = (unsigned)(uintptr_t)sK;
+        for (int blk16 = __builtin_amdgcn_readfirstlane(wave); blk16 < SK / 16; blk16 += kAttnThreads / 64) {
+            const int r = 16 * blk16 + (lane >> 2), c = (lane & 3) ^ ((r >> 2) & 3);
+            dma16(base + (long)r * ld + H + 16 * c, lds_k + 1024 * blk16);
+        }
+    } else {
+        for (int idx = tid; idx < SK * 4; idx += kAttnThreads) {
+            const int r = idx >> 2, c = idx & 3;
+            v4i kv = {0, 0, 0, 0};
+            if (r < S) kv = *reinterpret_cast<const v4i*>(base + (long)r * ld + H + 16 * c);
+            *reinterpret_cast<v4i*>(&sK[attn_koff(r, c)]) = kv;
+        }
     }
     // V tile -> LDS, transposed: a thread takes 4 keys x 16 head columns, transposes the bytes in
     // registers and writes one dword (4 keys of one column) per column.  Key r sits at position
@@ -139,6 +149,7 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
     const int m = bx * kQueries + wave * 16 + fr;
     v4i qf = {0, 0, 0, 0};
     if (kFull || m < S) qf = *reinterpret_cast<const v4i*>(base + (long)m * ld + 16 * hq);
+    if (kFull) wait_vmcnt<0>();   // this wavefront's K loads have landed (the barrier covers the others')
     __syncthreads();
 
     // ---- scores ---------------------------------------------------------------------------------

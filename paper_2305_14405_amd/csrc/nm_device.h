@@ -90,4 +90,21 @@ __device__ __forceinline__ void stage_table(float2* dst, const DevTable& t)
     for (int i = threadIdx.x; i < t.nseg; i += blockDim.x) dst[i] = t.kb[i];
 }
 
+// Direct global -> LDS load: every lane supplies its own global address of 16 bytes; the wavefront's
+// 1 KB lands contiguously at lds_addr (wave-uniform), lane i at lds_addr + 16*i.  Asynchronous:
+// completion is tracked by the vector-memory counter (wait_vmcnt), not by the LDS counter.
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(gptr)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 }  // namespace nm

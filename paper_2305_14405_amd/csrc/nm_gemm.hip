@@ -377,20 +377,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
 // output tiles: the A rows and W rows a block needs fit that XCD's L2.
 // int8 output goes through a per-wavefront LDS patch so that rows leave as 16-byte stores.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_addr), "v"(gptr)
-                 : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 // LDS offset of (row, 16-byte chunk) for rows of BK bytes.  BK = 64: four chunks, the swizzle of
 // the generic kernel.  BK = 128: eight chunks, 16 consecutive rows spread over all chunk positions
 // of two adjacent rows' worth of banks.
