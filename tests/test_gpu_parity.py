@@ -285,6 +285,32 @@ def test_gemm_int8_only_table_out_of_range(oracle, M, N, K, flags):
     assert_exact(host(oq), r["q"], f"gemm int8-only, table flags {flags}")
 
 
+@pytest.mark.parametrize("M,N,K,what", [
+    (6400, 64, 256, "narrow 256x64 tile"), (12800, 1024, 128, "two-stage 128x128 tile, several per CU"),
+    (12800, 1024, 512, "three-stage 128x128 tile, several per CU"), (640, 256, 1024, "64x128 split-k tile"),
+    (4099, 200, 384, "ragged edges on the streaming tiles"), (130, 136, 65536, "largest K")])
+def test_gemm_every_streaming_tile_configuration(oracle, M, N, K, what):
+    """Shapes that reach each tile configuration of the streaming kernel (chosen by the host from
+    M, N, K), full comparison of the int8 output with table, and of fp32 output with residual."""
+    ot, dt = both_tables(oracle, [("gelu", -8.0, 8.0, 128)])
+    d = W.gemm_inputs(M, N, K, seed=K + N, full_range=False)
+    alpha = float(np.float32(6.0 / (20 * 20 * np.sqrt(K))))
+    r = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, table=ot[0], out_inv_scale=25.0)
+    dA, dW, db, dr = dev(d["A"]), dev(d["W"]), dev(d["bias"]), dev(d["resid"])
+    oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, tables=dt, table_idx=0, out_inv_scale=25.0, out_q=oq)
+    assert_exact(host(oq), r["q"], f"int8 + table: {what}")
+    r2 = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, resid=d["resid"], resid_scale=0.02)
+    of = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, resid=dr, resid_scale=0.02, out_f32=of)
+    assert_f32_close(host(of), r2["y"], f"fp32 + residual: {what}")
+    r3 = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, resid=d["resid"], resid_scale=0.02,
+                         table=ot[0], out_inv_scale=25.0)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, resid=dr, resid_scale=0.02, tables=dt, table_idx=0,
+                   out_inv_scale=25.0, out_q=oq)
+    assert_exact(host(oq), r3["q"], f"int8 + residual + table: {what}")
+
+
 def test_gemm_extreme_operands(oracle):
     """All-(-127) x all-(+127) at the largest K of the workloads: |acc| = K * 127^2 > 2^24."""
     M, N, K = 40, 72, 3072
