@@ -54,6 +54,20 @@ __device__ __forceinline__ int attn_voff(int col) { return col * SV + (col >> 4)
 
 constexpr size_t attn_lds_bytes(int nkb) { return (size_t)nkb * 64 * 64 + 64 * ((size_t)nkb * 64 + 16) + 4 * 64; }
 
+// op(v, value of lane ^ MASK) for MASK 32 or 16 with the half / row swap instructions: swapping a
+// register with a copy of itself leaves {lower halves (even rows) twice} in one and {upper halves
+// (odd rows) twice} in the other; op is commutative, so op(first, second) is what every lane needs.
+template <int MASK, typename Op>
+__device__ __forceinline__ int swap_reduce(int v, Op op)
+{
+    if (MASK == 32) {
+        const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+        return op((int)r[0], (int)r[1]);
+    }
+    const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+    return op((int)r[0], (int)r[1]);
+}
+
 // 4x4 byte transpose: in[k] holds bytes (k, 0..3); out[c] holds bytes (0..3, c).
 __device__ __forceinline__ void transpose4x4(const unsigned in[4], unsigned out[4])
 {
@@ -184,8 +198,8 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if (kFull || 16 * blk + 4 * hq + e < S) mi = max(mi, acc[blk][e]);
-    mi = max(mi, __shfl_xor(mi, 32, 64));
-    mi = max(mi, __shfl_xor(mi, 16, 64));
+    mi = swap_reduce<32>(mi, [](int a, int b) { return max(a, b); });
+    mi = swap_reduce<16>(mi, [](int a, int b) { return max(a, b); });
 
     // exp values replace the scores in place (same registers, float bits).  Keys 256.. wrap onto
     // the 64 accumulators of keys 0..255 (accumulator = (key / 4) % 64) and continue their sums.
@@ -216,8 +230,9 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
 #pragma unroll
         for (int blk = 0; blk < mask; ++blk) part[blk] = part[blk] + part[blk + mask];
     float sum = part[0];
-    sum = sum + __shfl_xor(sum, 32, 64);
-    sum = sum + __shfl_xor(sum, 16, 64);
+    const auto addf = [](int a, int b) { return __float_as_int(__int_as_float(a) + __int_as_float(b)); };
+    sum = __int_as_float(swap_reduce<32>(__float_as_int(sum), addf));
+    sum = __int_as_float(swap_reduce<16>(__float_as_int(sum), addf));
     int segr;
     const float r = pwl_eval(sum, p.t_recip, s_kb_recip, segr);
 

@@ -195,3 +195,15 @@ def test_conv_and_pool_entry_points_validate_before_launch(lib):
     assert lib.nm_avgpool_i8(one, 1, 0, 8, 1.0, 1.0, one, None, z) == nm.NM_ERR_INVALID_ARG
     assert lib.nm_avgpool_i8(None, 1, 49, 8, 1.0, 1.0, one, None, z) == nm.NM_ERR_INVALID_ARG
     assert lib.nm_avgpool_i8(one, 1, 1 << 24, 8, 1.0, 1.0, one, None, z) == nm.NM_ERR_UNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message (before it
+    touches torch or the GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=60)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
