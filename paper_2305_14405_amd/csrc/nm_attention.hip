@@ -19,8 +19,11 @@
 // over the compute units than a 32x32 tiling would.
 // The int8 probabilities are packed in place, four per register, and four such registers ARE the
 // operand of the second product: the contraction index of an integer MFMA may be permuted freely
-// as long as both operands use the same permutation, so V^T is written to LDS with the key order
-// (64-key block, hq, blk % 4, e) that matches the way the probabilities sit in the lanes.
+// as long as both operands use the same permutation.  V stays row-major in LDS ([key][64 bytes],
+// copied like K); its operand fragments (one head column per lane, 16 keys) come out of the
+// transposing LDS read of gfx950 (ds_read_b64_tr_b8: within 16 lanes, lane j receives byte j % 8
+// of the eight rows addressed by lanes j / 8, j / 8 + 2, ...), with the row addresses chosen so
+// that the keys arrive in the order the probabilities have in the lanes.
 #include <climits>
 
 #include "nm_device.h"
@@ -47,12 +50,13 @@ constexpr int kHeadDim = 64;
 // K image: 64-byte rows, the four 16-byte chunks of a row rotated by (row / 4) % 4 so that the 16
 // lanes of an operand read (16 consecutive rows, one chunk) cover all banks.
 __device__ __forceinline__ int attn_koff(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); }
-// V^T image: one row per head column, SV bytes apart, plus 64 bytes after every 16 rows (spreads
-// the transposing writes over the banks).
-template <int SV>
-__device__ __forceinline__ int attn_voff(int col) { return col * SV + (col >> 4) * 64; }
+// V image: the same, with the rotation also depending on (row / 16) % 4, because one transposing
+// read touches rows 16 apart.
+__device__ __forceinline__ int attn_vswz(int row) { return ((row >> 2) & 3) ^ ((row >> 4) & 3); }
+__device__ __forceinline__ int attn_voff(int row, int chunk) { return row * 64 + ((chunk ^ attn_vswz(row)) << 4); }
 
-constexpr size_t attn_lds_bytes(int nkb) { return (size_t)nkb * 64 * 64 + 64 * ((size_t)nkb * 64 + 16) + 4 * 64; }
+constexpr int kCtxPatch = 16 * 80;   // per wavefront: 16 context rows of 64 bytes, 80 apart
+constexpr size_t attn_lds_bytes(int nkb) { return 2 * (size_t)nkb * 64 * 64 + (size_t)attn_waves(nkb) * kCtxPatch; }
 
 // op(v, value of lane ^ MASK) for MASK 32 or 16 with the half / row swap instructions: swapping a
 // register with a copy of itself leaves {lower halves (even rows) twice} in one and {upper halves
@@ -68,19 +72,6 @@ __device__ __forceinline__ int swap_reduce(int v, Op op)
     return op((int)r[0], (int)r[1]);
 }
 
-// 4x4 byte transpose: in[k] holds bytes (k, 0..3); out[c] holds bytes (0..3, c).
-__device__ __forceinline__ void transpose4x4(const unsigned in[4], unsigned out[4])
-{
-    const unsigned t0 = __builtin_amdgcn_perm(in[1], in[0], 0x05010400u);  // a0 b0 a1 b1
-    const unsigned t1 = __builtin_amdgcn_perm(in[3], in[2], 0x05010400u);  // c0 d0 c1 d1
-    const unsigned t2 = __builtin_amdgcn_perm(in[1], in[0], 0x07030602u);  // a2 b2 a3 b3
-    const unsigned t3 = __builtin_amdgcn_perm(in[3], in[2], 0x07030602u);  // c2 d2 c3 d3
-    out[0] = __builtin_amdgcn_perm(t1, t0, 0x05040100u);
-    out[1] = __builtin_amdgcn_perm(t1, t0, 0x07060302u);
-    out[2] = __builtin_amdgcn_perm(t3, t2, 0x05040100u);
-    out[3] = __builtin_amdgcn_perm(t3, t2, 0x07060302u);
-}
-
 // NKB: padded key count / 64.  kFull: S == 64 * NKB, so no key or query is masked (removes every
 // per-key predicate).
 template <int NKB, bool kFull>
@@ -90,10 +81,10 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
     constexpr int kQueries = 16 * attn_waves(NKB);   // queries per workgroup
     constexpr int SK = NKB * 64;   // padded key count
     constexpr int NBLK = SK / 16;  // 16-key blocks
-    constexpr int SV = SK + 16;    // row stride of the transposed V image
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     int8_t* sK = smem;
-    int8_t* sVt = smem + SK * 64;
+    int8_t* sV = smem + SK * 64;
+    int8_t* sO = smem + 2 * SK * 64;   // context patches
     float2* s_kb = reinterpret_cast<float2*>(smem + attn_lds_bytes(NKB));
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -120,43 +111,26 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
     float2* s_kb_recip = s_kb + p.t_exp.nseg;
     stage_table(s_kb, p.t_exp);
     stage_table(s_kb_recip, p.t_recip);
-    // K tile -> LDS.  With every row present the copy is a direct global -> LDS load (16 rows of
-    // 64 bytes per wavefront instruction; the chunk rotation is applied to the source address); it
-    // is in flight while V is transposed below.  Otherwise through registers, rows past S zero.
+    // K and V tiles -> LDS, row-major.  With every row present the copy is a direct global -> LDS
+    // load (16 rows of 64 bytes per wavefront instruction; the chunk rotation is applied to the
+    // source address).  Otherwise through registers: K rows past S are zero; V rows past S stay
+    // unwritten (they only ever meet zero probabilities).
     if (kFull) {
-        const unsigned lds_k = (unsigned)(uintptr_t)sK;
+        const unsigned lds_k = (unsigned)(uintptr_t)sK, lds_v = (unsigned)(uintptr_t)sV;
         for (int blk16 = __builtin_amdgcn_readfirstlane(wave); blk16 < SK / 16; blk16 += kAttnThreads / 64) {
-            const int r = 16 * blk16 + (lane >> 2), c = (lane & 3) ^ ((r >> 2) & 3);
-            dma16(base + (long)r * ld + H + 16 * c, lds_k + 1024 * blk16);
+            const int r = 16 * blk16 + (lane >> 2);
+            dma16(base + (long)r * ld + H + 16 * ((lane & 3) ^ ((r >> 2) & 3)), lds_k + 1024 * blk16);
+            dma16(base + (long)r * ld + 2 * H + 16 * ((lane & 3) ^ attn_vswz(r)), lds_v + 1024 * blk16);
         }
     } else {
         for (int idx = tid; idx < SK * 4; idx += kAttnThreads) {
             const int r = idx >> 2, c = idx & 3;
             v4i kv = {0, 0, 0, 0};
-            if (r < S) kv = *reinterpret_cast<const v4i*>(base + (long)r * ld + H + 16 * c);
+            if (r < S) {
+                kv = *reinterpret_cast<const v4i*>(base + (long)r * ld + H + 16 * c);
+                *reinterpret_cast<v4i*>(&sV[attn_voff(r, c)]) = *reinterpret_cast<const v4i*>(base + (long)r * ld + 2 * H + 16 * c);
+            }
             *reinterpret_cast<v4i*>(&sK[attn_koff(r, c)]) = kv;
-        }
-    }
-    // V tile -> LDS, transposed: a thread takes 4 keys x 16 head columns, transposes the bytes in
-    // registers and writes one dword (4 keys of one column) per column.  Key r sits at position
-    // 64*(r/64) + 16*((r/4)%4) + 4*((r/16)%4) + r%4 of its column's row.
-    for (int idx = tid; idx < SK; idx += kAttnThreads) {
-        const int r0 = (idx >> 2) * 4, c = idx & 3;
-        v4i vv[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            vv[k] = v4i{0, 0, 0, 0};
-            if (kFull || r0 + k < S) vv[k] = *reinterpret_cast<const v4i*>(base + (long)(r0 + k) * ld + 2 * H + 16 * c);
-        }
-        const int pos = (r0 & ~63) + 16 * ((r0 >> 2) & 3) + 4 * ((r0 >> 4) & 3);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const unsigned in[4] = {(unsigned)vv[0][q], (unsigned)vv[1][q], (unsigned)vv[2][q], (unsigned)vv[3][q]};
-            unsigned out[4];
-            transpose4x4(in, out);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                *reinterpret_cast<unsigned*>(&sVt[attn_voff<SV>(16 * c + 4 * q + e) + pos]) = out[e];
         }
     }
     // this lane's query row, straight from global memory into the MFMA operand registers
@@ -260,6 +234,19 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
     }
 
     // ---- context --------------------------------------------------------------------------------
+    // Operand slot s (0..15) of lane group hq must hold key 64*kb + 16*(s/4) + 4*hq + s%4 (where the
+    // probabilities sit).  A transposing read delivers eight rows: this lane supplies the address of
+    // row (lane % 16) / 2 of its group, shifted by 8 bytes for odd lanes so that lanes 8..15 of the
+    // group receive head columns 8..15.
+    typedef int v2i_t __attribute__((ext_vector_type(2)));
+    const int tr_t = fr >> 1, tr_half = fr & 1;
+    int voff[2];   // this lane's row address for the two reads of an operand (kb = 0, cb = 0)
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const int sidx = 8 * hh + tr_t;
+        const int key = 16 * (sidx >> 2) + 4 * hq + (sidx & 3);
+        voff[hh] = key * 64 + 8 * tr_half;   // chunk position added per product: (cb ^ hq ^ (sidx >> 2)) * 16
+    }
     v4i a2[4];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) a2[cb] = v4i{0, 0, 0, 0};
@@ -268,29 +255,42 @@ __global__ __launch_bounds__(64 * attn_waves(NKB)) __attribute__((amdgpu_waves_p
         const v4i pf = {(int)pk[4 * kb], (int)pk[4 * kb + 1], (int)pk[4 * kb + 2], (int)pk[4 * kb + 3]};
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
-            // product cb takes the head columns 16*(row/4) + 4*cb + row%4, so that lane (m, hq)
-            // collects columns 16*hq .. 16*hq+15 over the four products: one 16-byte store
-            const v4i vf = *reinterpret_cast<const v4i*>(
-                &sVt[attn_voff<SV>(16 * (fr >> 2) + 4 * cb + (fr & 3)) + 64 * kb + 16 * hq]);
+            v2i_t part[2];
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int chunk = cb ^ hq ^ ((8 * hh + tr_t) >> 2);
+                part[hh] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                    (__attribute__((address_space(3))) v2i_t*)(sV + 4096 * kb + voff[hh] + 16 * chunk));
+            }
+            const v4i vf = {part[0][0], part[0][1], part[1][0], part[1][1]};
             a2[cb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, a2[cb], 0, 0, 0);
         }
     }
-    if (kFull || m < S) {
-        const long orow = ((long)b * S + m) * H + head * kHeadDim;
-        v4i o;
+    // lane (m, hq) holds head columns 16*cb + 4*hq + e of query m: through a per-wavefront LDS patch
+    // so that every lane stores 16 consecutive bytes
+    int8_t* patch = sO + wave * kCtxPatch;
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-            int q[4];
+    for (int cb = 0; cb < 4; ++cb) {
+        int q[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                q[e] = requant(__builtin_fmaf((float)a2[cb][e], p.alpha_ctx, 0.0f), p.inv_s_ctx);
-            o[cb] = (int)pack4(q[0], q[1], q[2], q[3]);
-        }
-        if (p.ctx_vec16) {
-            *reinterpret_cast<v4i*>(p.ctx + orow + 16 * hq) = o;
-        } else {
+        for (int e = 0; e < 4; ++e)
+            q[e] = requant(__builtin_fmaf((float)a2[cb][e], p.alpha_ctx, 0.0f), p.inv_s_ctx);
+        *reinterpret_cast<unsigned*>(patch + fr * 80 + 16 * cb + 4 * hq) = pack4(q[0], q[1], q[2], q[3]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    {
+        const int mq = bx * kQueries + wave * 16 + (lane >> 2), c = lane & 3;
+        if (kFull || mq < S) {
+            const v4i o = *reinterpret_cast<const v4i*>(patch + (lane >> 2) * 80 + 16 * c);
+            int8_t* dst = p.ctx + ((long)b * S + mq) * H + head * kHeadDim + 16 * c;
+            if (p.ctx_vec16) {
+                *reinterpret_cast<v4i*>(dst) = o;
+            } else {
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb) *reinterpret_cast<int*>(p.ctx + orow + 16 * hq + 4 * cb) = o[cb];
+                for (int w = 0; w < 4; ++w) *reinterpret_cast<int*>(dst + 4 * w) = o[w];
+            }
         }
     }
 }
