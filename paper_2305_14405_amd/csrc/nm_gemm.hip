@@ -5,10 +5,14 @@
 // Paper basis: Section 3.1 (fully connected layers, attention and residual additions are matrix
 // multiplications / additions) and Section 3.2 (the nonlinearity after a linear operator is the
 // element-wise PWL calculation y = k[s]*x + b[s]).  The paper blocks its matrices for a systolic
-// array with a three-level buffer hierarchy; here the blocking is for CDNA4: a workgroup of four
-// wavefronts owns a BM x BN tile of the output, the k-loop streams 64-byte slices of both operands
-// through double-buffered LDS, and each wavefront issues 32x32x32 int8 MFMAs on its WM x WN
-// sub-tile with int32 accumulators that never leave registers until the epilogue.
+// array with a three-level buffer hierarchy; here the blocking is for CDNA4: a workgroup of four or
+// eight wavefronts owns a BM x BN tile of the output, the k-loop streams 64- or 128-byte slices of
+// both operands through a ring of LDS stages, and each wavefront issues 32x32x32 int8 MFMAs on its
+// WM x WN sub-tile with int32 accumulators that never leave registers until the epilogue.
+// Two kernels: gemm_stream_kernel (aligned operands, K a multiple of 64: operands go global -> LDS
+// directly; also gathers the rows of a convolution's patch matrix on the fly) in several tile
+// configurations chosen by launch_gemm, and gemm_pwl_kernel (any shape and alignment, W as [N,K]
+// or [K,N], operands through registers).
 //
 // Operand roles: the MFMA's first operand supplies the rows of its 32x32 result and the second
 // the columns.  W rows (output columns n) go first and A rows (output rows m) second, so a lane
@@ -364,14 +368,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Streaming kernel for the shapes of the encoder layer: K a multiple of 64, 16-byte aligned rows,
-// W as [N, K].  Operands go global -> LDS directly (global_load_lds_dwordx4: a wavefront
+// Streaming kernel: K a multiple of 64 (of BK), 16-byte aligned rows, W as [N, K].  Operands go global -> LDS directly (global_load_lds_dwordx4: a wavefront
 // instruction moves 64 x 16 bytes into 1 KB of consecutive LDS, no registers in between) through
 // a ring of kStages stages; a wavefront waits with an explicit vmcnt for the stage it is about to
 // use while the loads of the later stages stay in flight.  The LDS image of a stage is
-// (BM + BN) rows of 64 bytes: 16 consecutive rows per wavefront instruction, with the chunk
-// swizzle applied on the global side (lane p of an instruction fetches row p/4, logical chunk
-// (p%4) ^ swz(row)).  Rows past the matrix edge are clamped to the last row: they only feed
+// (BM + BN) rows of BK bytes: 1 KB of consecutive rows per wavefront instruction, with the chunk
+// swizzle applied on the global side (with 64-byte rows lane p of an instruction fetches row p/4,
+// logical chunk (p%4) ^ swz(row)).  Rows past the matrix edge are clamped to the last row: they only feed
 // accumulators that are never stored.
 // Workgroups are numbered so that the eight XCDs (workgroup id mod 8) each own a compact block of
 // output tiles: the A rows and W rows a block needs fit that XCD's L2.
