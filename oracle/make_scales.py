@@ -24,7 +24,7 @@ from paper_2305_14405_amd import workloads as W  # noqa: E402
 _FUNC = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
 # batch used for calibration: activations are i.i.d. over sequences, a few are enough
 CALIB_BATCH = {"bert_base_s512": 2, "bert_large_s512": 1}
-DEFAULT = ("tiny", "ragged", "bert_base_layer", "bert_base_s512", "bert_large_s512",
+DEFAULT = ("tiny", "ragged", "long_seq", "bert_base_layer", "bert_base_s512", "bert_large_s512",
            "resnet_tiny", "resnet_odd", "resnet50")
 RESNET_CALIB_BATCH = {"resnet50": 2}
 

@@ -35,6 +35,8 @@ CONFIGS = {
     "bert_base_s512": dict(B=16, S=512, H=768, heads=12, F=3072, nseg=128),
     # one layer of BASELINE config 4 (24-layer BERT-large, batch 32, sequence 512)
     "bert_large_s512": dict(B=32, S=512, H=1024, heads=16, F=4096, nseg=64),
+    # a sequence longer than the fused attention kernel covers (parity tests only: three-kernel attention)
+    "long_seq": dict(B=1, S=640, H=128, heads=2, F=256, nseg=64),
     # ragged shapes that fit no tile exactly (parity tests only)
     "ragged": dict(B=3, S=40, H=96, heads=3, F=200, nseg=37),
 }

@@ -473,7 +473,7 @@ def run_layer(oracle, name, library_tables=False, seed=0):
     return want, got
 
 
-@pytest.mark.parametrize("name", ["tiny", "ragged", "bert_base_layer"])
+@pytest.mark.parametrize("name", ["tiny", "ragged", "long_seq", "bert_base_layer"])
 def test_encoder_layer_all_stages(oracle, name):
     want, got = run_layer(oracle, name)
     for k in ("qkv", "scores", "p", "ctx", "ln1", "ffn1", "y_q"):
