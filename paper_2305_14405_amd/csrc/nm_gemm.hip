@@ -24,6 +24,7 @@
 // k of one row.  The same k of A and W always meet in the same (lane group, byte) slot, and int32
 // addition is exact, so results do not depend on tiling, on the k order or on any split of K.
 #include <cstdlib>
+#include <cstring>
 #include <type_traits>
 
 #include "nm_device.h"
@@ -77,11 +78,17 @@ static bool force_generic()
     static const bool v = [] { const char* e = getenv("NM_GEMM_GENERIC"); return e && e[0] == '1'; }();
     return v;
 }
-// Debug switch: NM_GEMM_TILE=mid keeps every shape on the 128x128 streaming tile.
-static bool force_mid_tile()
+// Debug switch, read at every call: NM_GEMM_CFG=big|wide|split|small|mid3|mid2 forces that tile
+// configuration of the streaming kernel wherever its requirements hold (tuning aid: lets one
+// process time the alternatives back to back).
+static int forced_cfg()
 {
-    static const bool v = [] { const char* e = getenv("NM_GEMM_TILE"); return e && e[0] == 'm'; }();
-    return v;
+    const char* e = getenv("NM_GEMM_CFG");
+    if (!e) return -1;
+    static const char* const names[] = {"big", "wide", "split", "small", "mid3", "mid2"};
+    for (int i = 0; i < 6; ++i)
+        if (!strcmp(e, names[i])) return i;
+    return -1;
 }
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 2) & 3); }
@@ -872,26 +879,40 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
         else if (only_q && g.resid && g.has_table && !g.table.clamp_input && p.vec_out) epi = EPI_Q_TABLE_RESID;
         else if (g.out_acc && !g.out_q && !g.out_f32) epi = EPI_ACC;
     }
-    // Tile configuration.  BIG (256x192, two 128-byte stages) when the output is wide and its tiles
-    // fill the chip; several small workgroups per CU (MID2 / MID3: 128x128, 64-byte slices, two or
-    // three stages, 32 / 48 KB of LDS) when there are at least three 128x128 tiles per CU, so that
-    // one workgroup's epilogue overlaps another's loads (WIDE: 256x128 with 128x64 wavefront
-    // tiles, one wavefront per SIMD and workgroup, 48 KB, for wide outputs whose 256x128 tiles come
-    // six to a CU: measured 7 % faster than BIG there, slower below); SPLIT (128x128, two wavefronts per
-    // sub-tile, 128-byte slices) when tiles are scarce, SMALL (64x128, same scheme) when even those
-    // would leave more than a third of the CUs idle; NARROW (256x64) for outputs of at most 64 columns.
+    // Tile configuration, from same-process timings of every configuration on the shapes of the
+    // workloads.  NARROW (256x64) for outputs of at most 64 columns.  Wide outputs (N >= 1536): BIG
+    // (256x192, two 128-byte stages, one workgroup per CU) when its tiles fill whole rounds of the
+    // 256 CUs to at least 90 %, WIDE (256x128 with 128x64 wavefront tiles, 48 KB ring) when those come six or more to a CU.
+    // Otherwise by the number of 128x128 tiles: three or more per CU -> MID2 (two 64-byte stages,
+    // 32 KB: four workgroups share a CU and one's epilogue overlaps another's loads); 1.25 to 3 per
+    // CU -> MID3 (three stages), or SMALL (64x128, two wavefronts per sub-tile on alternate
+    // k-steps, 128-byte slices) for long contractions; fewer -> SPLIT (128x128, same scheme), or
+    // SMALL when even those would leave more than a third of the CUs idle.
     const bool k128 = g.K % 128 == 0 && (!g.conv || g.cCin % 128 == 0);  // 128-byte k-slices fetch ~1.5x faster
     const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 191) / 192) * batches;
     const long mid_tiles = (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * batches;
     const long wide_tiles = (long)((g.M + 255) / 256) * ((g.N + 127) / 128) * batches;
-    const bool want_wide = wide_tiles >= 1536 && g.K > 256 && g.N >= 1536;
+    const bool split_ok = k128 && table_bytes <= 32768;
+    // share of CU slots the BIG tiles use over their rounds (one workgroup per CU; a single partly
+    // filled round counts as full: there is nothing better to do with the idle CUs)
+    const double big_fill = big_tiles <= 256 ? 1.0 : (double)big_tiles / (double)((big_tiles + 255) / 256 * 256);
     enum { CFG_BIG, CFG_WIDE, CFG_SPLIT, CFG_SMALL, CFG_MID3, CFG_MID2, CFG_NARROW } cfg;
     if (g.N <= 64) cfg = CFG_NARROW;
-    else if (want_wide) cfg = CFG_WIDE;
-    else if (!g.conv && k128 && g.N >= 1536 && big_tiles >= 192 && !force_mid_tile()) cfg = CFG_BIG;
-    else if (mid_tiles >= 768 && !force_mid_tile()) cfg = g.K <= 256 ? CFG_MID2 : CFG_MID3;
-    else if (k128 && table_bytes <= 32768) cfg = (mid_tiles < 160 && g.M > 64) ? CFG_SMALL : CFG_SPLIT;
+    else if (g.N >= 1536 && g.K > 256 && wide_tiles >= 1536) cfg = CFG_WIDE;
+    else if (!g.conv && k128 && g.N >= 1536 && big_tiles >= 192 && big_fill >= 0.9) cfg = CFG_BIG;
+    else if (mid_tiles >= 768) cfg = CFG_MID2;
+    else if (mid_tiles >= 320) cfg = (split_ok && g.K >= 2048) ? CFG_SMALL : CFG_MID3;
+    else if (split_ok) cfg = (mid_tiles < 160 && g.M > 64) ? CFG_SMALL : CFG_SPLIT;
     else cfg = CFG_MID3;
+    if (g.N > 64) {
+        const int f = forced_cfg();
+        if (f == 0 && !g.conv && k128) cfg = CFG_BIG;
+        else if (f == 1) cfg = CFG_WIDE;
+        else if (f == 2 && split_ok) cfg = CFG_SPLIT;
+        else if (f == 3 && split_ok) cfg = CFG_SMALL;
+        else if (f == 4) cfg = CFG_MID3;
+        else if (f == 5) cfg = CFG_MID2;
+    }
     if (g.conv) {
         // gathered A operand: streaming kernel only (the caller has checked Cin % 64 == 0, 16-byte
         // aligned image and weights); one problem, no batching
