@@ -314,7 +314,7 @@ def main():
     out = dict(metric="PWL encoder-layer sequences/s + int8 MFMA util % + nonlinear-kernel HBM GB/s",
                value=round(seq_per_s, 1), unit="sequences/s", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True,
-               scaling="weak", vs_baseline=None, dtype="int8 (int32 accumulate, fp32 epilogue)",
+               scaling="weak", vs_baseline=None, dtype="int8", dtype_note="int8 operands, int32 accumulation, fp32 epilogue",
                data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
                                              nseg=cfg["nseg"], layers=n_layers),
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
@@ -511,7 +511,7 @@ def bench_resnet(args):
     out = dict(metric="PWL encoder-layer sequences/s + int8 MFMA util % + nonlinear-kernel HBM GB/s",
                value=round(B / (ms_per_step * 1e-3), 1), unit="images/s", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True, scaling="weak",
-               vs_baseline=None, dtype="int8 (int32 accumulate, fp32 epilogue)", data="synthetic",
+               vs_baseline=None, dtype="int8", dtype_note="int8 operands, int32 accumulation, fp32 epilogue", data="synthetic",
                config=dict(workload=args.workload, B=B, image=cfg["HW"], stages=list(cfg["stages"]),
                            widths=list(cfg["widths"]), classes=cfg["classes"], launch=launch_mode,
                            ms_per_step_eager=round(ms_eager, 5)),
