@@ -249,3 +249,29 @@ def test_cnn_run_matches_oracle_network(oracle):
     with pytest.raises(nm.NmError) as ei:
         nm.nm_cnn_run([bad], ws)
     assert ei.value.status == nm.NM_ERR_INVALID_ARG
+
+
+def test_conv2d_unaligned_operands_take_the_patch_matrix_route(oracle):
+    """A 64-channel convolution whose image or filter pointer is not 16-byte aligned cannot use the
+    gathered loader: it needs a workspace and still matches the oracle."""
+    g = np.random.default_rng(77)
+    B, H, Wd, Cin, Cout = 2, 10, 9, 64, 80
+    x = rand_i8(g, (B, H, Wd, Cin), 50)
+    w = rand_i8(g, (Cout, 3, 3, Cin), 50)
+    ot, dt = relu_tables(oracle)
+    av = np.full(Cout, 2e-4, np.float32)
+    r = oracle.conv2d_pwl(x, w, stride=1, pad=1, alpha_vec=av, table=ot, out_inv_scale=20.0, want_acc=False)
+    raw = torch.zeros(x.size + 32, dtype=torch.int8, device=DEV)
+    raw[8:8 + x.size] = dev(x).view(-1)            # data starts 8 bytes after an aligned address
+    dx = raw[8:8 + x.size].view(B, H, Wd, Cin)
+    dw, dav = dev(w), dev(av)
+    oq = torch.empty((B, H, Wd, Cout), dtype=torch.int8, device=DEV)
+    d = nm.make_conv_desc(dx, dw, 1, 1, alpha_vec=dav, tables=dt, table_idx=0, out_inv_scale=20.0, out_q=oq)
+    need = nm.nm_conv2d_workspace(d)
+    assert need == B * H * Wd * 576 + Cout * 576
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    nm.nm_conv2d_pwl(d, ws)
+    assert np.array_equal(host(oq), r["q"])
+    # aligned again: no workspace
+    d2 = nm.make_conv_desc(dev(x), dw, 1, 1, alpha_vec=dav, tables=dt, table_idx=0, out_inv_scale=20.0, out_q=oq)
+    assert nm.nm_conv2d_workspace(d2) == 0

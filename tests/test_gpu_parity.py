@@ -549,3 +549,32 @@ def test_workspace_errors():
     assert ei.value.status == nm.NM_ERR_WORKSPACE
     d2, k, b, inv_w = nm.nm_tables_get(dt, 1)
     assert d2.nseg == specs[1][3] and k.shape == (specs[1][3],) and nm.nm_tables_count(dt) == 4
+
+
+def test_gemm_misaligned_pointers(oracle):
+    """Operands and outputs that start one byte / one element off an aligned address: the generic
+    kernel with scalar accesses must give the same result as the aligned fast path."""
+    M, N, K = 70, 132, 192
+    d = W.gemm_inputs(M, N, K, seed=5, full_range=False)
+    ot, dt = both_tables(oracle, [("gelu", -8.0, 8.0, 64)])
+    alpha = float(np.float32(6.0 / (20 * 20 * np.sqrt(K))))
+    r = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, resid=d["resid"], resid_scale=0.02,
+                        table=ot[0], out_inv_scale=25.0)
+
+    def off(a, dtype):
+        raw = torch.zeros(a.size + 8, dtype=dtype, device=DEV)
+        raw[1:1 + a.size] = dev(a).view(-1)
+        return raw, raw[1:1 + a.size].view(*a.shape)
+
+    keepA, dA = off(d["A"], torch.int8)
+    keepW, dW = off(d["W"], torch.int8)
+    keepb, db = off(d["bias"], torch.float32)
+    keepr, dr = off(d["resid"], torch.int8)
+    rawq = torch.zeros(M * N + 8, dtype=torch.int8, device=DEV)
+    rawf = torch.zeros(M * N + 8, dtype=torch.float32, device=DEV)
+    oq, of = rawq[3:3 + M * N].view(M, N), rawf[1:1 + M * N].view(M, N)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, resid=dr, resid_scale=0.02, tables=dt, table_idx=0,
+                   out_inv_scale=25.0, out_q=oq, out_f32=of)
+    assert_exact(host(oq), r["q"], "misaligned gemm int8")
+    assert_f32_close(host(of), r["y"], "misaligned gemm fp32")
+    assert int(host(rawq)[:3].any()) == 0 and int(host(rawq)[3 + M * N:].any()) == 0  # nothing written outside
