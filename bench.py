@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--workload", default="bert_base_layer")
     ap.add_argument("--layers", type=int, default=0, help="stack depth (0: the workload's own)")
     ap.add_argument("--nseg", type=int, default=0, help="segments per table (0: the workload's own)")
+    ap.add_argument("--table-flags", type=int, default=0,
+                    help="table construction flags for every table (2: the paper's Algorithm 3 bias correction)")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -97,7 +99,7 @@ def main():
     B, S, H, nh, F = (cfg[k] for k in ("B", "S", "H", "heads", "F"))
     M, d = B * S, cfg["H"] // cfg["heads"]
     order = ("gelu", "exp", "recip", "rsqrt")
-    specs = [W.table_ranges(cfg)[n] for n in order]
+    specs = [tuple(W.table_ranges(cfg)[n]) + (args.table_flags,) for n in order]
     tables = nm.nm_build_tables(specs)          # the library's own table builder
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)  # noqa: E731
     devws = [{n: t(q[n]) for n in nm.LAYER_PTRS} for q in stack]
@@ -272,7 +274,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import oracle as O
         oid = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
-        ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3]) for n, s in zip(order, specs)}
+        ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3], flags=args.table_flags) for n, s in zip(order, specs)}
         # bounded sample: whole batch for the 128-token layer, two sequences of layer 0 otherwise
         # (sequences are independent, so a batch subset is the same computation on fewer rows)
         b_sub = B if (n_layers == 1 and M * H <= 4096 * 768) else min(B, 2)
@@ -316,7 +318,8 @@ def main():
                warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True,
                scaling="weak", vs_baseline=None, dtype="int8", dtype_note="int8 operands, int32 accumulation, fp32 epilogue",
                data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
-                                             nseg=cfg["nseg"], layers=n_layers),
+                                             nseg=cfg["nseg"], layers=n_layers,
+                                             table_flags=args.table_flags),
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
                summary=summary,
                parity=parity)
