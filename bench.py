@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--nseg", type=int, default=0, help="segments per table (0: the workload's own)")
     ap.add_argument("--table-flags", type=int, default=0,
                     help="table construction flags for every table (2: the paper's Algorithm 3 bias correction)")
+    ap.add_argument("--dk-th", type=float, default=0.0,
+                    help="slope threshold of the paper's Algorithm 2 (with --table-flags 4: neighbouring "
+                         "primary segments whose slopes differ by less are merged)")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -99,7 +102,9 @@ def main():
     B, S, H, nh, F = (cfg[k] for k in ("B", "S", "H", "heads", "F"))
     M, d = B * S, cfg["H"] // cfg["heads"]
     order = ("gelu", "exp", "recip", "rsqrt")
-    specs = [tuple(W.table_ranges(cfg)[n]) + (args.table_flags,) for n in order]
+    specs = [tuple(W.table_ranges(cfg)[n]) + (args.table_flags, 0.0, args.dk_th) for n in order]
+    # distinct {k, b} pairs per table: what Algorithm 2's merging leaves of the primary segments
+    distinct = {n: int(nm.nm_table_build_host(sp)[3]) for n, sp in zip(order, specs)}
     tables = nm.nm_build_tables(specs)          # the library's own table builder
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)  # noqa: E731
     devws = [{n: t(q[n]) for n in nm.LAYER_PTRS} for q in stack]
@@ -274,7 +279,11 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import oracle as O
         oid = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
-        ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3], flags=args.table_flags) for n, s in zip(order, specs)}
+        if args.table_flags & 4:
+            ot = {n: O.build_table_merged(oid[s[0]], s[1], s[2], s[3], args.dk_th, flags=args.table_flags & ~4)[0]
+                  for n, s in zip(order, specs)}
+        else:
+            ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3], flags=args.table_flags) for n, s in zip(order, specs)}
         # bounded sample: whole batch for the 128-token layer, two sequences of layer 0 otherwise
         # (sequences are independent, so a batch subset is the same computation on fewer rows)
         b_sub = B if (n_layers == 1 and M * H <= 4096 * 768) else min(B, 2)
@@ -319,7 +328,8 @@ def main():
                scaling="weak", vs_baseline=None, dtype="int8", dtype_note="int8 operands, int32 accumulation, fp32 epilogue",
                data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
                                              nseg=cfg["nseg"], layers=n_layers,
-                                             table_flags=args.table_flags),
+                                             table_flags=args.table_flags, dk_th=args.dk_th,
+                                             distinct_segments=distinct),
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
                summary=summary,
                parity=parity)
