@@ -293,7 +293,7 @@ def main():
         while True:
             want = O.encoder_layer(p_sub, ot, x_sub, want_taps=False)
             n_runs += 1
-            if time.perf_counter() - c0 > 10.0 or n_runs >= 8:
+            if time.perf_counter() - c0 > 12.0 or n_runs >= 64:
                 break
         cpu_s = (time.perf_counter() - c0) / n_runs
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
