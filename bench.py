@@ -505,7 +505,7 @@ def bench_resnet(args):
     cpu_baseline = parity = None
     if not args.no_cpu_baseline:
         from oracle import oracle as O
-        b_sub = min(B, 2)
+        b_sub = B   # the whole batch: about ten seconds of oracle time at batch 64
         p_sub = W.resnet_params(args.workload, 0, batch=b_sub)
         c0 = time.perf_counter()
         want = O.resnet_forward(p_sub)["logits"]
