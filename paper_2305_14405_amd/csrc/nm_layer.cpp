@@ -21,6 +21,11 @@ struct LayerPlan {
     size_t off_qkv, off_scores, off_p, off_ctx, off_attn, off_ln1, off_ffn1, off_ffn2, total;
 };
 
+static bool fused_attention_shape(const nm_layer_desc* d)
+{
+    return d->H / d->heads == 64 && d->S <= 512 && d->H % 16 == 0 && !unfused_attention();
+}
+
 static LayerPlan plan_layer(const nm_layer_desc* d)
 {
     const size_t M = (size_t)d->B * d->S, H = d->H, F = d->F;
@@ -29,8 +34,12 @@ static LayerPlan plan_layer(const nm_layer_desc* d)
     size_t o = 0;
     auto take = [&o](size_t bytes) { size_t at = o; o = round_up(o + bytes, 256); return at; };
     p.off_qkv = take(M * 3 * H);
-    p.off_scores = take(SS * sizeof(int32_t));
-    p.off_p = take(SS);
+    // the score and probability tensors exist only on the three-kernel attention path (the fused
+    // kernel keeps them in registers; every workspace tensor is 256-byte aligned, so whether it
+    // runs depends on the shape alone)
+    const bool fused = fused_attention_shape(d);
+    p.off_scores = take(fused ? 0 : SS * sizeof(int32_t));
+    p.off_p = take(fused ? 0 : SS);
     p.off_ctx = take(M * H);
     p.off_attn = take(M * H * sizeof(float));
     p.off_ln1 = take(M * H);
@@ -118,8 +127,15 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
     }
     // 2-4: attention.  One fused kernel when the shape allows it (the scores and probabilities then
     // stay in registers; the taps, if given, still receive them), else three kernels.
-    const bool fused = H / nh == 64 && S <= 512 && H % 16 == 0 && aligned(qkv, 16) && aligned(ctx, 4) &&
-                       (!(taps && taps->scores) || aligned(taps->scores, 16)) && !unfused_attention();
+    // taps supplied by the caller replace workspace tensors and may be less aligned: the fused
+    // kernel then still runs if they are aligned enough, else the three-kernel path needs the
+    // caller's score / probability taps as storage (the workspace has none for a fused shape)
+    bool fused = fused_attention_shape(d);
+    if (fused && !(aligned(qkv, 16) && aligned(ctx, 4) && (!(taps && taps->scores) || aligned(taps->scores, 16)))) {
+        if (!(taps && taps->scores && taps->p))
+            return fail(NM_ERR_UNSUPPORTED, "nm_encoder_layer: qkv / ctx / scores taps must be 16-byte aligned");
+        fused = false;
+    }
     if (fused) {
         if ((rc = nm_attention_pwl(qkv, B, S, H, nh, d->alpha_scores, d->tables, d->exp_idx, d->recip_idx,
                                    d->inv_s_p, d->alpha_ctx, d->inv_s_ctx, ctx, taps ? taps->scores : nullptr,

@@ -126,8 +126,16 @@ def test_compute_entry_points_validate_before_launch(lib):
     ld.B, ld.S, ld.H, ld.heads, ld.F = 32, 128, 768, 12, 3072
     assert lib.nm_encoder_layer_workspace(C.byref(ld), C.byref(n)) == nm.NM_OK
     M, H, F, SS = 4096, 768, 3072, 32 * 12 * 128 * 128
-    need = M * 3 * H + SS * 4 + SS + M * H + M * H * 4 + M * H + M * F + M * H * 4
+    # head size 64 and S <= 512: the fused attention kernel keeps scores and probabilities in registers
+    need = M * 3 * H + M * H + M * H * 4 + M * H + M * F + M * H * 4
     assert need <= n.value <= need + 8 * 256
+    ld2 = nm.LayerDesc()
+    ld2.B, ld2.S, ld2.H, ld2.heads, ld2.F = 2, 640, 128, 2, 256      # S > 512: three-kernel attention
+    n2 = C.c_size_t()
+    assert lib.nm_encoder_layer_workspace(C.byref(ld2), C.byref(n2)) == nm.NM_OK
+    M2, SS2 = 1280, 2 * 2 * 640 * 640
+    need2 = M2 * 3 * 128 + SS2 * 4 + SS2 + M2 * 128 + M2 * 128 * 4 + M2 * 128 + M2 * 256 + M2 * 128 * 4
+    assert need2 <= n2.value <= need2 + 8 * 256
     assert lib.nm_encoder_layer(C.byref(ld), one, one, None, one, n, None, z) == nm.NM_ERR_INVALID_ARG
     # stack: two activation buffers on top of the largest layer workspace; layers must agree on B, S, H
     arr = (nm.LayerDesc * 3)()
