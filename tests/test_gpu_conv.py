@@ -42,6 +42,9 @@ CASES = [  # B, H, W, Cin, Cout, kh, kw, stride, pad   (route)
     (2, 9, 11, 12, 20, 3, 3, 1, 1),       # odd channel counts: patch matrix, unaligned GEMM
     (1, 5, 5, 64, 64, 5, 5, 1, 2),        # filter as large as the image
     (33, 7, 7, 64, 64, 3, 3, 1, 1),       # many images, tile edge in M
+    (2, 11, 11, 64, 48, 3, 3, 1, 1),      # gathered operand, fewer than 64 output channels
+    (2, 10, 10, 128, 100, 3, 3, 1, 1),    # output channels not a multiple of 16 (no 16-byte row stores)
+    (1, 30, 30, 64, 72, 1, 1, 3, 0),      # stride 3
 ]
 
 
