@@ -303,6 +303,19 @@ def main():
             sample += f"; value = {b_sub} / ({n_layers} layers x {cpu_s:.2f} s), extrapolated linearly over layers"
         cpu_baseline = dict(value=round(b_sub / (cpu_s * n_layers), 4), unit="sequences/s", cores=cores,
                             kind="oracle", sample=sample)
+        # the same on one thread (one sequence, one run), for the per-core figure
+        try:
+            import ctypes
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            p_one = dict(p, B=1)
+            c1 = time.perf_counter()
+            O.encoder_layer(p_one, ot, np.ascontiguousarray(p["x"][:S]), want_taps=False)
+            one_s = time.perf_counter() - c1
+            gomp.omp_set_num_threads(cores)
+            cpu_baseline["value_1_thread"] = round(1.0 / (one_s * n_layers), 4)
+        except OSError:
+            pass
         # layer 0 on the GPU (library-built tables) against the oracle's layer 0 (oracle-built tables:
         # may differ in the last bit), and against the oracle's true-function mode (same quantised
         # network, exact GELU / exp / 1/x / rsqrt in binary64): the PWL approximation error
