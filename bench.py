@@ -374,7 +374,7 @@ def graph_timed(torch, fn, reps):
 
 
 def bench_resnet(args):
-    """BASELINE config 3: the ResNet-50-shaped int8 network (convolutions in matrix form, folded
+    """benchmark configuration 3: the ResNet-50-shaped int8 network (convolutions in matrix form, folded
     batch norm, ReLU as a two-segment PWL table), one C-ABI call per operation.  value = images/s."""
     import numpy as np
     import torch

@@ -27,13 +27,13 @@ SCALES_JSON = os.path.join(_HERE, "workload_scales.json")
 
 # name -> dims, segment count, PWL ranges (function name, lo, hi)
 CONFIGS = {
-    # BASELINE config 0: the small case the oracle finishes in well under a second
+    # benchmark configuration 0: the small case the oracle finishes in well under a second
     "tiny": dict(B=1, S=64, H=128, heads=2, F=512, nseg=64),
-    # BASELINE config 1: the configuration the headline metric is quoted on
+    # benchmark configuration 1: the configuration the headline metric is quoted on
     "bert_base_layer": dict(B=32, S=128, H=768, heads=12, F=3072, nseg=128),
-    # one layer of BASELINE config 2 (12-layer BERT-base, batch 16, sequence 512)
+    # one layer of benchmark configuration 2 (12-layer BERT-base, batch 16, sequence 512)
     "bert_base_s512": dict(B=16, S=512, H=768, heads=12, F=3072, nseg=128),
-    # one layer of BASELINE config 4 (24-layer BERT-large, batch 32, sequence 512)
+    # one layer of benchmark configuration 4 (24-layer BERT-large, batch 32, sequence 512)
     "bert_large_s512": dict(B=32, S=512, H=1024, heads=16, F=4096, nseg=64),
     # a sequence longer than the fused attention kernel covers (parity tests only: three-kernel attention)
     "long_seq": dict(B=1, S=640, H=128, heads=2, F=256, nseg=64),
@@ -53,7 +53,7 @@ def config(name: str) -> dict:
 
 
 def table_ranges(cfg: dict) -> dict:
-    """PWL ranges of BASELINE's configs: GELU on [-8, 8], exp on [-16, 0], reciprocal on
+    """PWL ranges of the benchmark's configurations: GELU on [-8, 8], exp on [-16, 0], reciprocal on
     [1, max(64, S)] (a softmax denominator lies in [1, S]), rsqrt on [1e-3, 64]."""
     n = int(cfg["nseg"])
     return {
@@ -217,7 +217,7 @@ def sweep_values(lo: float, hi: float, n: int, seed: int = 0) -> np.ndarray:
 
 
 # ---------------------------------------------------------------------------------------------
-# Residual CNN workload (BASELINE config 3: ResNet-50-shaped network as int8 convolutions in
+# Residual CNN workload (benchmark configuration 3: ResNet-50-shaped network as int8 convolutions in
 # their matrix form, batch normalisation folded into a per-channel scale and bias, ReLU as a
 # two-segment PWL table).  Stand-in for the paper's ResNet-50 / ImageNet experiments: random
 # weights, inputs U(0, 1).
