@@ -314,7 +314,8 @@ static int32_t plan_conv(const nm_conv_desc* d, const char* what, ConvPlan* pl)
     pl->K16 = (int)((K + 63) / 64 * 64);  // whole 64-byte k-slices: the streaming GEMM runs on the patch matrix
     pl->M = (long)M;
     const bool plain = d->kh == 1 && d->kw == 1 && d->stride == 1 && d->pad == 0;
-    const bool gather = d->Cin % 64 == 0 && aligned(d->x, 16) && aligned(d->w, 16);
+    const bool gather = d->Cin % 64 == 0 && aligned(d->x, 16) && aligned(d->w, 16) &&
+                        (int64_t)d->H * d->W * d->Cin < (1LL << 31);   // 32-bit offsets inside one image
     // direct kernel: few input channels, a filter row fits 32 bytes, int8 output only
     const bool direct = !plain && d->Cin <= 4 && d->kw <= 8 && d->Cout <= 64 && d->Cout % 16 == 0 && d->out_q &&
                         !d->out_f32 && !d->dbg_acc && !d->resid && aligned(d->out_q, 16) &&

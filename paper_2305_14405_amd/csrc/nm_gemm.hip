@@ -533,6 +533,7 @@ void gemm_stream_kernel(GemmParams p)
     // kConv: slices are issued in increasing kt, so the tap (ti, tj) and the channel offset tc of
     // the slice being issued are kept as running (wave-uniform) counters.
     int ti = 0, tj = 0, tc = 0;
+    const int8_t* zero_src = g_zero_line + 16 * (lane % CPR);
     auto issue = [&](int kt, int stage, int part, int parts) {
         const unsigned dst = lds_base + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
@@ -540,10 +541,12 @@ void gemm_stream_kernel(GemmParams p)
             if (b % parts == part && (b < LB - 1 || has_last)) {
                 const int blk = wave + b * NW;
                 if (kConv && blk * RPI < BM) {  // wave-uniform: an A block
+                    // offsets inside one image fit 32 bits (checked on the host): cheap integer
+                    // arithmetic and one select instead of 64-bit multiplies under a branch
                     const int hi = conv_h[b] + ti, wi = conv_w[b] + tj;
                     const bool inside = (unsigned)hi < (unsigned)p.cH && (unsigned)wi < (unsigned)p.cW;
-                    const int8_t* g = inside ? src[b] + ((long)hi * p.cW + wi) * p.cCin + tc
-                                             : g_zero_line + 16 * (lane % CPR);
+                    const int off = (hi * p.cW + wi) * p.cCin + tc;
+                    const int8_t* g = inside ? src[b] + off : zero_src;
                     dma16(g, dst + b * NW * 1024);
                 } else {
                     dma16(src[b] + (long)kt * BK, dst + b * NW * 1024);
