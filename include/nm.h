@@ -1,8 +1,9 @@
 /*
  * nm.h -- C ABI of the MI355X (gfx950) NeuralMatrix inference library.
  *
- * The library computes a transformer encoder layer with linear matrix operations only (paper,
- * Section 3): every linear operator is an int8 x int8 -> int32 matrix product (Section 3.1) and
+ * The library computes transformer encoder layers (and residual CNNs, as convolutions in matrix
+ * form) with linear matrix operations only (paper, Section 3): every linear operator is an
+ * int8 x int8 -> int32 matrix product (Section 3.1) and
  * every nonlinear operator (GELU, the exponential and the reciprocal of softmax, the reciprocal
  * square root of LayerNorm) is a piecewise-linear table y = k[s]*x + b[s] whose segment s is found
  * by quantising x (Section 3.2, Post-Training Approximation; Algorithm 3 for k, b; Algorithm 2
