@@ -315,6 +315,22 @@ int32_t nm_encoder_layer_workspace(const nm_layer_desc* desc, size_t* bytes);
 int32_t nm_encoder_layer(const nm_layer_desc* desc, const int8_t* x, int8_t* y_q, float* y_f32,
                          void* ws, size_t ws_bytes, const nm_layer_taps* taps, void* stream);
 
+/*
+ * nm_encoder_layer_noalloc: nm_encoder_layer for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation): the workspace is
+ * a buffer of NM_NOALLOC_MAX_WORKSPACE bytes built into the library's device image (each GPU the
+ * library runs on holds one until the process ends), so the caller passes inputs and outputs only.
+ * Same results as nm_encoder_layer, no taps.  Calls nothing that allocates or frees.
+ * Returns NM_ERR_WORKSPACE (message says how much is needed) when nm_encoder_layer_workspace of
+ * the shape exceeds NM_NOALLOC_MAX_WORKSPACE: B32 S128 H768 F3072 fits, B16 S512 H768 does not.
+ * Every call on a GPU uses that GPU's one buffer, whose contents are scratch and survive from call
+ * to call (nothing in it needs to start at zero): two calls that overlap in time on the same GPU,
+ * from different streams or threads, race.  Calls on one stream are ordered and safe.
+ */
+#define NM_NOALLOC_MAX_WORKSPACE (64u << 20)
+int32_t nm_encoder_layer_noalloc(const nm_layer_desc* desc, const int8_t* x, int8_t* y_q, float* y_f32,
+                                 void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * nm_encoder_stack: n_layers encoder layers back to back on one stream (the paper's Section 4
  * models are stacks of identical layers: 12 for BERT-base, 24 for BERT-large).  Layer l reads the

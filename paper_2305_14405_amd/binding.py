@@ -23,9 +23,11 @@ EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_table
            "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_destroy",
            "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_layernorm_pwl2", "nm_pwl_apply", "nm_attn_scores",
            "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer",
+           "nm_encoder_layer_noalloc",
            "nm_encoder_stack_workspace", "nm_encoder_stack", "nm_conv2d_workspace", "nm_conv2d_pwl",
            "nm_maxpool_i8", "nm_avgpool_i8", "nm_cnn_workspace", "nm_cnn_run")
 NM_OP_CONV, NM_OP_MAXPOOL, NM_OP_AVGPOOL, NM_OP_GEMM = 0, 1, 2, 3
+NM_NOALLOC_MAX_WORKSPACE = 64 << 20  # bytes of the buffer built into the library (nm_encoder_layer_noalloc)
 
 
 class NmError(RuntimeError):
@@ -137,6 +139,8 @@ def load(preload_torch: bool = True) -> C.CDLL:
     L.nm_encoder_layer_workspace.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_size_t)]
     L.nm_encoder_layer.argtypes = [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.POINTER(LayerTaps), C.c_void_p]
+    L.nm_encoder_layer_noalloc.argtypes = [C.POINTER(LayerDesc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p]
     L.nm_conv2d_workspace.argtypes = [C.POINTER(ConvDesc), C.POINTER(C.c_size_t)]
     L.nm_conv2d_pwl.argtypes = [C.POINTER(ConvDesc), C.c_void_p, C.c_size_t, C.c_void_p]
     L.nm_maxpool_i8.argtypes = [C.c_void_p] + [C.c_int32] * 7 + [C.c_void_p, C.c_void_p]
@@ -357,6 +361,10 @@ def nm_encoder_layer(desc: LayerDesc, x, y_q, y_f32, ws, taps: dict | None = Non
     nbytes = ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes
     _check(load().nm_encoder_layer(C.byref(desc), _ptr(x), _ptr(y_q), _ptr(y_f32), _ptr(ws), nbytes,
                                    C.byref(ct) if ct is not None else None, _stream(stream)))
+
+
+def nm_encoder_layer_noalloc(desc: LayerDesc, x, y_q, y_f32, stream=None):
+    _check(load().nm_encoder_layer_noalloc(C.byref(desc), _ptr(x), _ptr(y_q), _ptr(y_f32), _stream(stream)))
 
 
 def _desc_array(descs):

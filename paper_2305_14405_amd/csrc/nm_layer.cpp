@@ -3,6 +3,7 @@
 // operators as PWL tables).  Host code only: it validates, carves the workspace and queues the
 // nine steps; nothing is allocated and the host never waits for the GPU.
 #include <cstdlib>
+#include <mutex>
 
 #include "nm_internal.h"
 
@@ -63,6 +64,36 @@ static int32_t validate_layer(const nm_layer_desc* d, const char* what)
     const int64_t M = (int64_t)d->B * d->S;
     if (M * 3 * d->H >= (1LL << 31) || M * d->F >= (1LL << 31))
         return fail(NM_ERR_UNSUPPORTED, "%s: B*S*max(3H, F) >= 2^31", what);
+    return NM_OK;
+}
+
+// ---- scratch of the entry point that allocates nothing --------------------------------------
+// One array per GPU, in the library's own device image (zero-initialised storage, so it adds
+// nothing to the file).  Host code never uses the array's name as an address: the device address is
+// looked up once per device and cached.
+constexpr size_t kStaticScratchBytes = (size_t)NM_NOALLOC_MAX_WORKSPACE;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the current device's copy of `scratch`.
+static int32_t static_scratch(void** out)
+{
+    int dev = -1;
+    int32_t rc = check_hip(hipGetDevice(&dev), "hipGetDevice");
+    if (rc) return rc;
+    if (dev < 0 || dev >= kMaxDevices) return fail(NM_ERR_UNSUPPORTED, "device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        rc = check_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (rc) return rc;
+        if (!ptr) return fail(NM_ERR_HIP, "hipGetSymbolAddress(scratch) returned NULL");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
     return NM_OK;
 }
 
@@ -186,6 +217,20 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
     // 9: LayerNorm-PWL -> layer output
     return launch_layernorm(ffn2, d->gamma2, d->beta2, d->eps2, M, H, t_rsqrt, d->inv_s_out, y_q, y_f32,
                             nullptr, stream);
+}
+
+int32_t nm_encoder_layer_noalloc(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, float* y_f32, void* stream)
+{
+    int32_t rc = validate_layer(d, "nm_encoder_layer_noalloc");
+    if (rc) return rc;
+    const size_t need = plan_layer(d).total;
+    if (need > kStaticScratchBytes)
+        return fail(NM_ERR_WORKSPACE,
+                    "nm_encoder_layer_noalloc: this shape needs %zu bytes of scratch, the built-in buffer holds %zu "
+                    "(use nm_encoder_layer with a workspace of your own)", need, kStaticScratchBytes);
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws))) return rc;
+    return nm_encoder_layer(d, x, y_q, y_f32, ws, kStaticScratchBytes, nullptr, stream);
 }
 
 // ---- stack of layers -------------------------------------------------------------------------

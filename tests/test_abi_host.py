@@ -137,6 +137,13 @@ def test_compute_entry_points_validate_before_launch(lib):
     need2 = M2 * 3 * 128 + SS2 * 4 + SS2 + M2 * 128 + M2 * 128 * 4 + M2 * 128 + M2 * 256 + M2 * 128 * 4
     assert need2 <= n2.value <= need2 + 8 * 256
     assert lib.nm_encoder_layer(C.byref(ld), one, one, None, one, n, None, z) == nm.NM_ERR_INVALID_ARG
+    # the entry point that allocates nothing: validation and the size limit come before any GPU call
+    assert lib.nm_encoder_layer_noalloc(None, one, one, None, z) == nm.NM_ERR_INVALID_ARG
+    ld3 = nm.LayerDesc()
+    ld3.B, ld3.S, ld3.H, ld3.heads, ld3.F = 16, 512, 768, 12, 3072
+    assert lib.nm_encoder_layer_noalloc(C.byref(ld3), one, one, None, z) == nm.NM_ERR_WORKSPACE
+    assert b"built-in buffer" in lib.nm_last_error()
+    assert n.value <= nm.NM_NOALLOC_MAX_WORKSPACE
     # stack: two activation buffers on top of the largest layer workspace; layers must agree on B, S, H
     arr = (nm.LayerDesc * 3)()
     for i in range(3):
