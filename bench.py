@@ -88,7 +88,7 @@ def main():
     import torch
 
     from paper_2305_14405_amd import binding as nm
-    from paper_2305_14405_amd import workloads as W
+    import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
@@ -385,7 +385,7 @@ def bench_resnet(args):
     import torch
 
     from paper_2305_14405_amd import binding as nm
-    from paper_2305_14405_amd import workloads as W
+    import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2305_14405_amd import binding as nm
-from paper_2305_14405_amd import workloads as W
+import workloads as W
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"

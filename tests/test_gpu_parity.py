@@ -9,7 +9,7 @@ import pytest
 import torch
 
 from paper_2305_14405_amd import binding as nm
-from paper_2305_14405_amd import workloads as W
+import workloads as W
 
 pytestmark = pytest.mark.gpu
 
@@ -115,6 +115,102 @@ def test_clamp_input_flag(oracle):
     nm.nm_pwl_apply(dev(x), 1.0, dt, 0, 100.0, out_f32=yf, dbg_seg=ys)
     assert_exact(host(ys).view(np.uint16), s, "clamp seg")
     assert_f32_close(host(yf), y, "clamp fp32")
+
+
+# ---- tables built with Algorithm 3 (bias correction) and Algorithm 2 (segment merging) ---------
+
+# (label, library flags, e_th, dk_th)
+ELASTIC = [("bias", nm.NM_TABLE_BIAS_CORRECT, 0.0, 0.0),
+           ("bias_threshold", nm.NM_TABLE_BIAS_CORRECT, 2e-3, 0.0),
+           ("merge", nm.NM_TABLE_MERGE, 0.0, 0.02),
+           ("merge_bias", nm.NM_TABLE_MERGE | nm.NM_TABLE_BIAS_CORRECT, 0.0, 0.02)]
+
+
+def elastic_tables(oracle, specs, flags, e_th, dk_th):
+    """Oracle tables built with the given options, a device object holding exactly their k, b, and
+    a device object the library built itself from the same descriptors."""
+    oflags = oracle.FLAG_BIAS_CORRECT if flags & nm.NM_TABLE_BIAS_CORRECT else 0
+    ot = []
+    for (f, lo, hi, n) in specs:
+        if flags & nm.NM_TABLE_MERGE:
+            t, n_merged = oracle.build_table_merged(OID[f], lo, hi, n, dk_th, flags=oflags, e_th=e_th)
+            assert 1 <= n_merged <= n
+        else:
+            t = oracle.build_table(OID[f], lo, hi, n, flags=oflags, e_th=e_th)
+        ot.append(t)
+    injected = nm.nm_tables_from_arrays([(f, lo, hi, n, 0) for (f, lo, hi, n) in specs],
+                                        [t.k for t in ot], [t.b for t in ot])
+    built = nm.nm_build_tables([(f, lo, hi, n, flags, e_th, dk_th) for (f, lo, hi, n) in specs])
+    return ot, injected, built
+
+
+ELASTIC_SPECS = [("gelu", -8.0, 8.0, 128), ("exp", -16.0, 0.0, 64), ("recip", 1.0, 64.0, 64),
+                 ("rsqrt", 1e-3, 64.0, 256)]
+
+
+@pytest.mark.parametrize("label,flags,e_th,dk_th", ELASTIC)
+def test_elastic_tables_pwl_apply(oracle, label, flags, e_th, dk_th):
+    """nm_pwl_apply on tables built with Algorithm 3 / Algorithm 2: exact with the oracle's arrays
+    injected, within one int8 code with the tables the library builds itself."""
+    ot, injected, built = elastic_tables(oracle, ELASTIC_SPECS, flags, e_th, dk_th)
+    plain = [oracle.build_table(OID[f], lo, hi, n) for (f, lo, hi, n) in ELASTIC_SPECS]
+    changed = 0
+    for ti, (f, lo, hi, n) in enumerate(ELASTIC_SPECS):
+        changed += int(not (np.array_equal(ot[ti].k, plain[ti].k) and np.array_equal(ot[ti].b, plain[ti].b)))
+        x = W.sweep_values(lo, hi, 50021, seed=40 + ti)
+        y, q, s = oracle.pwl_apply(x, ot[ti], out_inv_scale=11.0)
+        yq = torch.empty(x.size, dtype=torch.int8, device=DEV)
+        yf = torch.empty(x.size, dtype=torch.float32, device=DEV)
+        ys = torch.empty(x.size, dtype=torch.int16, device=DEV)
+        nm.nm_pwl_apply(dev(x), 1.0, injected, ti, 11.0, out_q=yq, out_f32=yf, dbg_seg=ys)
+        assert_exact(host(ys).view(np.uint16), s, f"{label} {f} segments")
+        assert_exact(host(yq), q, f"{label} {f} int8")
+        assert_f32_close(host(yf), y, f"{label} {f} fp32")
+        nm.nm_pwl_apply(dev(x), 1.0, built, ti, 11.0, out_q=yq, dbg_seg=ys)
+        assert_exact(host(ys).view(np.uint16), s, f"{label} {f} segments, library-built table")
+        d = np.abs(host(yq).astype(int) - q.astype(int))
+        assert d.max() <= 1 and (d > 0).mean() < 1e-3, f"{label} {f}: library-built table off by {d.max()}"
+    # the options did change the tables (with a threshold only where a segment's bias exceeds it)
+    assert changed == len(ELASTIC_SPECS) or (e_th > 0 and changed >= 1)
+
+
+@pytest.mark.parametrize("label,flags,e_th,dk_th", ELASTIC)
+def test_elastic_tables_gemm_epilogue(oracle, label, flags, e_th, dk_th):
+    """nm_gemm_pwl with a GELU table built with Algorithm 3 / Algorithm 2 (streaming and generic
+    kernels)."""
+    ot, injected, built = elastic_tables(oracle, [("gelu", -8.0, 8.0, 128)], flags, e_th, dk_th)
+    for (M, N, K) in [(256, 384, 256), (70, 50, 96)]:
+        d = W.gemm_inputs(M, N, K, seed=M + K, full_range=False)
+        alpha = float(np.float32(6.0 / (20 * 20 * np.sqrt(K))))
+        r = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, table=ot[0], out_inv_scale=25.0)
+        oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+        seg = torch.empty((M, N), dtype=torch.int16, device=DEV)
+        nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=injected,
+                       table_idx=0, out_inv_scale=25.0, out_q=oq, dbg_seg=seg)
+        assert_exact(host(seg).view(np.uint16), r["seg"], f"{label} gemm segments")
+        assert_exact(host(oq), r["q"], f"{label} gemm int8")
+        oq2 = torch.empty_like(oq)
+        nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=injected,
+                       table_idx=0, out_inv_scale=25.0, out_q=oq2)       # the specialised epilogue
+        assert_exact(host(oq2), r["q"], f"{label} gemm int8, specialised epilogue")
+        nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=built,
+                       table_idx=0, out_inv_scale=25.0, out_q=oq2)
+        diff = np.abs(host(oq2).astype(int) - r["q"].astype(int))
+        assert diff.max() <= 1 and (diff > 0).mean() < 1e-3
+
+
+@pytest.mark.parametrize("label,flags,e_th,dk_th", ELASTIC)
+def test_elastic_tables_encoder_layer(oracle, label, flags, e_th, dk_th):
+    """The tiny encoder layer with all four tables built with Algorithm 3 / Algorithm 2."""
+    want, got = run_layer(oracle, "tiny", elastic=(flags, e_th, dk_th))
+    for k in ("qkv", "scores", "p", "ctx", "ln1", "ffn1", "y_q"):
+        assert_exact(got[k], want[k], f"{label} tiny layer {k}")
+    for k in ("attn", "ffn2", "y_f32"):
+        assert_f32_close(got[k], want[k], f"{label} tiny layer {k}")
+    want, got = run_layer(oracle, "tiny", library_tables=True, elastic=(flags, e_th, dk_th))
+    diff = np.abs(got["y_q"].astype(int) - want["y_q"].astype(int))
+    assert diff.max() <= 1 and (diff > 0).mean() < 2e-3
+    assert np.allclose(got["y_f32"], want["y_f32"], rtol=1e-4, atol=1e-5)
 
 
 # ---- softmax-PWL ------------------------------------------------------------------------------
@@ -439,13 +535,18 @@ def test_fused_attention_unsupported_shapes():
 
 # ---- encoder layer ----------------------------------------------------------------------------
 
-def run_layer(oracle, name, library_tables=False, seed=0):
+def run_layer(oracle, name, library_tables=False, seed=0, elastic=None):
     cfg = W.config(name)
     p = W.layer_params(name, seed)
     specs = [W.table_ranges(cfg)[n] for n in ("gelu", "exp", "recip", "rsqrt")]
-    ot, dt = both_tables(oracle, specs)
-    if library_tables:
-        dt = nm.nm_build_tables(specs)
+    if elastic is None:
+        ot, dt = both_tables(oracle, specs)
+        if library_tables:
+            dt = nm.nm_build_tables(specs)
+    else:
+        ot, dt, dt_lib = elastic_tables(oracle, specs, *elastic)
+        if library_tables:
+            dt = dt_lib
     tb = dict(zip(("gelu", "exp", "recip", "rsqrt"), ot))
     want = oracle.encoder_layer(p, tb, p["x"])
     B, S, H, nh, F = (cfg[k] for k in ("B", "S", "H", "heads", "F"))
@@ -520,6 +621,35 @@ def test_encoder_stack(oracle, name, n_layers):
     with pytest.raises(nm.NmError) as ei:
         nm.nm_encoder_stack(descs, dev(ps[0]["x"]), yq, None, ws, ws_bytes=ws.numel() - 1)
     assert ei.value.status == nm.NM_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("name,n_layers,batch", [("bert_base_s512", 12, None), ("bert_large_s512", 24, 8)])
+def test_encoder_stack_full_depth(oracle, name, n_layers, batch):
+    """The 12-layer and the 24-layer workloads at their full depth, every layer with weights and
+    calibrated scales of its own: int8 output exact after all requantisations.  The 12-layer stack
+    runs its full batch; the 24-layer one 8 of its 32 sequences (the oracle's share of the time)."""
+    cfg = W.config(name)
+    ps = W.stack_params(name, n_layers)
+    B = cfg["B"] if batch is None else batch
+    x = ps[0]["x"][: B * cfg["S"]]
+    for p in ps:
+        p["B"] = B
+    specs = [W.table_ranges(cfg)[n] for n in ("gelu", "exp", "recip", "rsqrt")]
+    ot, dt = both_tables(oracle, specs)
+    want = oracle.encoder_stack(ps, dict(zip(("gelu", "exp", "recip", "rsqrt"), ot)), x)
+    keep, descs = [], []
+    for p in ps:
+        devw = {n: dev(p[n]) for n in nm.LAYER_PTRS}
+        keep.append(devw)
+        descs.append(nm.make_layer_desc(p, devw, dt))
+    M, H = B * cfg["S"], cfg["H"]
+    ws = torch.empty(nm.nm_encoder_stack_workspace(descs), dtype=torch.uint8, device=DEV)
+    yq = torch.empty((M, H), dtype=torch.int8, device=DEV)
+    yf = torch.empty((M, H), dtype=torch.float32, device=DEV)
+    nm.nm_encoder_stack(descs, dev(x), yq, yf, ws)
+    assert_exact(host(yq), want["y_q"], f"{name} x{n_layers} stack output")
+    assert_f32_close(host(yf), want["y_f32"], f"{name} x{n_layers} stack fp32 output")
+    assert len(np.unique(want["y_q"])) > 100  # the stack's output is not degenerate
 
 
 def test_encoder_layer_with_library_built_tables(oracle):

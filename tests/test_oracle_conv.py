@@ -134,7 +134,7 @@ def test_resnet_forward_tracks_a_float64_library_network(oracle, name):
     operators and no activation rounding (weights dequantised, batch-norm gain and bias applied
     per channel, ReLU, residual sums, pooling, classifier): the wiring (strides, shortcuts,
     which tensor feeds which) must agree, so the logits differ only by quantisation noise."""
-    from paper_2305_14405_amd import workloads as W
+    import workloads as W
     p = W.resnet_params(name, 0)
     got = oracle.resnet_forward(p)["logits"]
     F = torch.nn.functional

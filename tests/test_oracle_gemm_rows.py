@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2305_14405_amd import workloads as W
+import workloads as W
 
 
 # ---- integer GEMM -------------------------------------------------------------------------------

@@ -9,7 +9,7 @@ import pytest
 import torch
 import torch.nn.functional as F
 
-from paper_2305_14405_amd import workloads as W
+import workloads as W
 
 FUNC = {"gelu": 0, "exp": 1, "recip": 2, "rsqrt": 3}
 

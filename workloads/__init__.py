@@ -1,5 +1,5 @@
 """Seeded synthetic workloads: the only module shared by the GPU library's harness and the CPU
-oracle's tests.  It generates INPUTS (int8 tensors, fp32 vectors, scale numbers, table ranges); it
+oracle's tests (a package of its own, outside both).  It generates INPUTS (int8 tensors, fp32 vectors, scale numbers, table ranges); it
 holds none of the method's arithmetic (no GEMM, no PWL evaluation, no reductions).
 
 The tensors stand in for the workloads the paper evaluates (BERT / RoBERTa encoders on GLUE):
@@ -146,19 +146,29 @@ def layer_params(name: str, seed: int = 0) -> dict:
     return with_scales(layer_tensors(config(name), seed), stored_scales(name, seed))
 
 
+def stored_stack_scales(name: str, n_layers: int) -> list:
+    """Calibrated activation scales of every layer of a stack, from the stored calibration file."""
+    with open(SCALES_JSON) as f:
+        table = json.load(f)
+    key = f"{name}/stack"
+    if key not in table or len(table[key]) < n_layers:
+        raise KeyError(f"no stored activation scales for {n_layers} layers of {name}; run "
+                       f"python -m oracle.make_scales stack:{name}:{n_layers}")
+    return [{n: float(s[n]) for n in ACT_NAMES} for s in table[key][:n_layers]]
+
+
 def stack_params(name: str, n_layers: int) -> list:
-    """A stack of ``n_layers`` layers of a named workload: layer l has its own weights (seed l) and
-    reads the int8 output of layer l-1, so its input scale is that layer's output scale.  The
-    activation scales are the calibrated ones of layer 0 for every layer (each layer's input is a
-    LayerNorm output with the same statistics).  Element 0 also carries the stack input ``x``."""
-    cfg, act = config(name), stored_scales(name, 0)
+    """A stack of ``n_layers`` layers of a named workload: layer l has its own weights (seed l), its
+    own calibrated activation scales, and reads the int8 output of layer l-1, so its input scale is
+    that layer's output scale.  Element 0 also carries the stack input ``x``."""
+    cfg, acts = config(name), stored_stack_scales(name, n_layers)
     out = []
     for l in range(n_layers):
         t = layer_tensors(cfg, l)
         if l > 0:
             del t["x"]
-            t["s_x"] = act["out"]
-        out.append(with_scales(t, act))
+            t["s_x"] = acts[l - 1]["out"]
+        out.append(with_scales(t, acts[l]))
     return out
 
 
