@@ -93,12 +93,18 @@ __device__ __forceinline__ void stage_table(float2* dst, const DevTable& t)
 // Direct global -> LDS load: every lane supplies its own global address of 16 bytes; the wavefront's
 // 1 KB lands contiguously at lds_addr (wave-uniform), lane i at lds_addr + 16*i.  Asynchronous:
 // completion is tracked by the vector-memory counter (wait_vmcnt), not by the LDS counter.
+// The LDS address travels in M0, which is an operand of the statement (the register allocator
+// knows it is written here); one wait state separates the M0 write from its use.
 __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_addr), "v"(gptr)
-                 : "memory");
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "{m0}"(lds_addr) : "memory");
+}
+
+// The same with a wave-uniform base pointer and a 32-bit per-lane byte offset (the k-loop then
+// advances one scalar pointer instead of one 64-bit address per lane and load).
+__device__ __forceinline__ void dma16s(const void* sbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sbase), "{m0}"(lds_addr) : "memory");
 }
 
 template <int N>
