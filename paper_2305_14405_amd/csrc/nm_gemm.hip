@@ -25,54 +25,16 @@
 // addition is exact, so results do not depend on tiling, on the k order or on any split of K.
 #include <cstdlib>
 #include <cstring>
-#include <mutex>
-#include <type_traits>
 
-#include "nm_device.h"
+#include "nm_gemm_common.h"
+#include "nm_gemm_tile.h"
 
 namespace nm {
-
-constexpr int kGemmThreads = 256;
-constexpr int kBK = 64;  // bytes of k per pipeline stage
-
-struct GemmParams {
-    int M, N, K;
-    const int8_t* A; long lda;
-    const int8_t* W; long ldw;
-    int inner_count;
-    long a_outer, a_inner, w_outer, w_inner, o_outer, o_inner;
-    const float* bias;
-    const float* alpha_vec;
-    float alpha;
-    const int8_t* resid;
-    float resid_scale;
-    int has_table;
-    DevTable table;
-    float out_inv_scale;
-    const float* out_inv_scale_vec;
-    int split_cols;
-    float inv3[3];
-    long ldo;
-    int vec_out;
-    int q16;       // int8 output rows may be written with 16-byte stores
-    int r16;       // int8 residual rows may be read with 16-byte loads (and N % 16 == 0)
-    int vec_cols;  // bias / per-column scale vectors may be read with 16-byte loads
-    int8_t* out_q;
-    float* out_f32;
-    int32_t* out_acc;
-    uint16_t* dbg_seg;
-    int tiles_m, tiles_n;
-    // convolution in matrix form (streaming kernel with kConv): row m of A is the output position
-    // (b, ho, wo), column k the (tap, channel) pair; A points to the NHWC image tensor
-    int cH, cW, cCin, cKw, cStride, cPad, cHo, cWo;
-};
 
 // A line of zeros in device memory: the source of operand bytes that fall into a convolution's
 // padding (the direct global -> LDS loads cannot substitute a value, only an address).
 __device__ __attribute__((aligned(256))) int8_t g_zero_line[256];
 
-// XOR swizzle of the 16-byte chunk index inside a 64-byte LDS row: rows that fall into the same
-// bank window get different chunk positions, for both a 128-byte and a 256-byte wide LDS port.
 // Debug switch: NM_GEMM_GENERIC=1 in the environment sends every shape to the generic kernel.
 static bool force_generic()
 {
@@ -94,10 +56,6 @@ static int forced_cfg()
     }();
     return v;
 }
-
-__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 2) & 3); }
-
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * kBK + ((chunk ^ swz(row)) << 4); }
 
 // 16 bytes of a row-major int8 matrix at (row, k .. k+15); zeros outside [0,nrows) x [0,K).
 template <bool kAligned>
@@ -130,10 +88,6 @@ __device__ __forceinline__ v4i load_chunk(const int8_t* __restrict__ X, long ld,
 // Epilogue specialisations: the generic one reads every option at run time; the others fix the
 // set of outputs and options the encoder layer uses, which removes dead code from the unrolled
 // epilogue (it is instantiated once per accumulator group).
-enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4, EPI_Q_TABLE_RESID = 5 };
-// EPI_Q_TABLE_RESID: int8 residual, table (no input clamp), int8 output: the last convolution of a
-// residual block (sum with the shortcut, ReLU).
-
 struct Epi4 {
     float y[4];
     int q[4];
@@ -394,17 +348,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
 // LDS offset of (row, 16-byte chunk) for rows of BK bytes.  BK = 64: four chunks, the swizzle of
 // the generic kernel.  BK = 128: eight chunks, 16 consecutive rows spread over all chunk positions
 // of two adjacent rows' worth of banks.
-template <int BK>
-__device__ __forceinline__ int swz_bk(int row)
-{
-    return BK == 64 ? swz(row) : ((row >> 1) & 7);
-}
-template <int BK>
-__device__ __forceinline__ int lds_off_bk(int row, int chunk)
-{
-    return row * BK + ((chunk ^ swz_bk<BK>(row)) << 4);
-}
-
 // KSPLIT = 2 doubles the wavefronts of a workgroup without shrinking the wavefront tile: two
 // wavefronts share each WM x WN sub-tile and take alternate 32-byte k-steps of every k-slice (so
 // the LDS read traffic and the operand traffic stay those of the KSPLIT = 1 kernel, while each
@@ -787,362 +730,6 @@ void gemm_stream_kernel(GemmParams p)
     else finish_rows(std::false_type{});
 }
 
-// ---------------------------------------------------------------------------------------------
-// Tile kernel: the large-tile path for the plain matrix products of the encoder layer (aligned
-// operands, K a multiple of 128, scalar alpha, int8 output with or without the table, or fp32
-// output with the int8 residual).  Same LDS image and MFMA operand roles as the streaming kernel;
-// what differs is how the instruction stream is laid out:
-//  * the k-loop is software-pipelined by hand and its issue order is pinned with scheduling
-//    barriers: one matrix instruction, then at most one LDS fragment read (for the NEXT k-step, into
-//    the other of two fragment register sets) and one global -> LDS load in its shadow.  A wavefront
-//    therefore never waits for a fragment it has just asked for, and the one barrier per k-slice
-//    sits in the middle of a k-step whose fragments are already in registers;
-//  * a k-slice's ring slot is refilled right after that barrier (all of its fragments have been
-//    read by then), addresses are one scalar base per operand plus a 32-bit lane offset;
-//  * first slice, steady state and the last slices are straight-line code around one loop, so the
-//    accumulators stay in the same registers throughout;
-//  * the per-column vectors and the table are fetched when the kernel starts but written to LDS
-//    after the k-loop (nothing in front of the first operand slice waits for them);
-//  * the epilogue works on groups of four columns; the table look-up of a group is issued three
-//    groups before its result is used, and int8 rows leave through an LDS patch as 16-byte stores.
-// Eight wavefronts as 4 x 2 (64 x 96 each) keep two wavefronts on every SIMD: the fp32 epilogue
-// issues almost twice as fast that way as with four wavefronts of 128 x 96 (measured: a single
-// wavefront cannot issue dependent-free vector instructions back to back at the SIMD's full rate).
-// ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int kEpi>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(GemmParams p)
-{
-    constexpr int BK = 128;
-    constexpr int NW = WAVES_M * WAVES_N;
-    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-    constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int ROWS = BM + BN;
-    constexpr int CPR = BK / 16;
-    constexpr int RPI = 64 / CPR;
-    constexpr int NBLK = ROWS / RPI;
-    constexpr int LB = NBLK / NW;            // 1 KB blocks per wavefront and k-slice
-    constexpr int LBA = (BM / RPI) / NW;     // ... of which A rows
-    constexpr int STAGE_BYTES = ROWS * BK;
-    constexpr int KS = BK / 32;
-    constexpr int NR = TM + TN;              // fragments per k-step
-    constexpr int NMF = TM * TN;             // matrix instructions per k-step
-    constexpr int HALF = NMF - NR;           // ... of the last k-step in front of the slice barrier
-    constexpr int FIRST = NMF - HALF;        // refill blocks issued behind it; the rest in the next k-step
-    static_assert(NBLK % NW == 0 && (BM / RPI) % NW == 0, "blocks split evenly");
-    static_assert(LB - FIRST <= NMF && NR <= FIRST && HALF >= 1, "issue slots");
-    static_assert(kEpi == EPI_Q || kEpi == EPI_Q_TABLE || kEpi == EPI_F32_RESID, "epilogues of the tile kernel");
-
-    extern __shared__ __attribute__((aligned(16))) int8_t smem[];
-    float* s_bias = reinterpret_cast<float*>(smem + STAGES * STAGE_BYTES);
-    float2* s_kb = reinterpret_cast<float2*>(s_bias + BN);
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_m = (wave / WAVES_N) * WM;
-    const int wave_n = (wave % WAVES_N) * WN;
-
-    // XCD-aware tile order, as in the streaming kernel
-    int id = blockIdx.x;
-    const int ntiles = p.tiles_m * p.tiles_n;
-    if (ntiles % 8 == 0) id = (id % 8) * (ntiles / 8) + id / 8;
-    constexpr int GM = 8;
-    const int group = id / (GM * p.tiles_n);
-    const int first_m = group * GM;
-    const int gm = min(GM, p.tiles_m - first_m);
-    const int in_group = id - group * GM * p.tiles_n;
-    const int tile_m = first_m + in_group % gm;
-    const int tile_n = in_group / gm;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-    // per-lane byte offsets of this wavefront's blocks (rows past the edge are clamped: they only
-    // feed accumulators that are never stored); M * K and N * K fit 32 bits (host)
-    unsigned voff[LB];
-#pragma unroll
-    for (int b = 0; b < LB; ++b) {
-        const int blk = wave + b * NW;
-        const int r = blk * RPI + lane / CPR;
-        const int chunk = (lane % CPR) ^ swz_bk<BK>(r);
-        if (b < LBA) voff[b] = (unsigned)min(m0 + r, p.M - 1) * (unsigned)p.lda + 16u * chunk;
-        else voff[b] = (unsigned)min(n0 + r - BM, p.N - 1) * (unsigned)p.ldw + 16u * chunk;
-    }
-    const unsigned lds_base = (unsigned)(uintptr_t)smem;
-    const int8_t* __restrict__ gA = p.A;
-    const int8_t* __restrict__ gW = p.W;
-    auto issue1 = [&](int kt, int slot, int b) {
-        const unsigned dst = lds_base + slot * STAGE_BYTES + (wave + b * NW) * 1024;
-        dma16s((b < LBA ? gA : gW) + (long)kt * BK, voff[b], dst);
-    };
-    const int nk = p.K / BK;  // >= STAGES + 1 (host)
-#pragma unroll
-    for (int st = 0; st < STAGES; ++st)
-#pragma unroll
-        for (int b = 0; b < LB; ++b) issue1(st, st, b);
-
-    // epilogue parameters: fetched now, parked in registers until the k-loop is over
-    constexpr int BPT = (BN + 64 * NW - 1) / (64 * NW);
-    float bias_reg[BPT];
-#pragma unroll
-    for (int t = 0; t < BPT; ++t) {
-        const int c = tid + t * 64 * NW;
-        bias_reg[t] = (p.bias && c < BN && n0 + c < p.N) ? p.bias[n0 + c] : 0.0f;
-    }
-    constexpr int KPT = 4;  // table entries per thread held in registers (more are staged late)
-    float2 kb_reg[KPT];
-    if (kEpi == EPI_Q_TABLE) {
-#pragma unroll
-        for (int t = 0; t < KPT; ++t) {
-            const int e = tid + t * 64 * NW;
-            kb_reg[t] = e < p.table.nseg ? p.table.kb[e] : make_float2(0.0f, 0.0f);
-        }
-    }
-
-    // the int8 residual tile (fp32 epilogue) as 16-byte row pieces
-    constexpr int CPRW = BN / 16;
-    constexpr int RPT = (BM * CPRW + 64 * NW - 1) / (64 * NW);
-    v4i res_reg[RPT];
-    if (kEpi == EPI_F32_RESID) {
-#pragma unroll
-        for (int t = 0; t < RPT; ++t) {
-            const int c = tid + t * 64 * NW, row = c / CPRW, cc = c % CPRW;
-            const int mr = m0 + row, n = n0 + 16 * cc;
-            res_reg[t] = v4i{0, 0, 0, 0};
-            if (c < BM * CPRW && mr < p.M && n < p.N) res_reg[t] = *reinterpret_cast<const v4i*>(p.resid + (long)mr * p.ldo + n);
-        }
-    }
-
-    v16i acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
-
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    int offA[KS], offW[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        const int ra = wave_m + frag_row, rw = wave_n + frag_row;
-        offA[ks] = lds_off_bk<BK>(ra, 2 * ks + frag_half);
-        offW[ks] = BM * BK + lds_off_bk<BK>(rw, 2 * ks + frag_half);
-    }
-    v4i fa[2][TM], fw[2][TN];
-    // fragment t of a k-step, in the order the matrix instructions of that k-step need them
-    auto ldfrag1 = [&](int buf, int slot, int ks, int t) {
-        const int8_t* st = smem + slot * STAGE_BYTES;
-        if (t == 0) fw[buf][0] = *reinterpret_cast<const v4i*>(st + offW[ks]);
-        else if (t == 1) fa[buf][0] = *reinterpret_cast<const v4i*>(st + offA[ks]);
-        else if (t < 1 + TN) fw[buf][t - 1] = *reinterpret_cast<const v4i*>(st + offW[ks] + (t - 1) * 32 * BK);
-        else fa[buf][t - TN] = *reinterpret_cast<const v4i*>(st + offA[ks] + (t - TN) * 32 * BK);
-    };
-
-    // k-slice 0 has landed (the younger slices of the prologue stay in flight)
-    wait_vmcnt<(STAGES - 1) * LB>();
-    __syncthreads();
-#pragma unroll
-    for (int t = 0; t < NR; ++t) ldfrag1(0, 0, 0, t);
-
-    int slot = 0, pslot = 0;
-    // One k-slice.  MORE: slice kt + STAGES exists and refills this slice's slot (first blocks);
-    // MOREP: the rest of the refill begun during the previous slice; YOUNG: slices younger than
-    // kt + 1 in flight when kt + 1 is awaited (-1: there is no slice kt + 1).
-    auto slice = [&](auto more_c, auto morep_c, auto young_c, int kt) {
-        constexpr bool MORE = decltype(more_c)::value, MOREP = decltype(morep_c)::value;
-        constexpr int YOUNG = decltype(young_c)::value;
-        const int nslot = slot + 1 == STAGES ? 0 : slot + 1;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int cur = ks & 1;
-#pragma unroll
-            for (int t = 0; t < NMF; ++t) {
-                const int i = t / TN, j = t % TN;
-                if (ks == KS - 1 && t == HALF && YOUNG >= 0) {
-                    // every wavefront has read all of slice kt (its last fragments were requested
-                    // during the previous k-step); slice kt + 1 has landed for this wavefront
-                    wait_vmcnt<(YOUNG > 0 ? YOUNG : 0) * LB>();
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
-                if (ks < KS - 1) {
-                    if (t < NR) ldfrag1(cur ^ 1, slot, ks + 1, t);
-                    if (MOREP && ks == 0 && FIRST + t < LB) issue1(kt - 1 + STAGES, pslot, FIRST + t);
-                } else {
-                    if (YOUNG >= 0 && t >= HALF && t - HALF < NR) ldfrag1(cur ^ 1, nslot, 0, t - HALF);
-                    if (MORE && t >= HALF && t - HALF < LB) issue1(kt + STAGES, slot, t - HALF);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        pslot = slot;
-        slot = nslot;
-    };
-    using T_ = std::true_type;
-    using F_ = std::false_type;
-    slice(T_{}, F_{}, std::integral_constant<int, STAGES - 2>{}, 0);
-    for (int kt = 1; kt < nk - STAGES; ++kt) slice(T_{}, T_{}, std::integral_constant<int, STAGES - 2>{}, kt);
-    slice(F_{}, T_{}, std::integral_constant<int, STAGES - 2>{}, nk - STAGES);
-    auto tail = [&](auto self, auto r_c) -> void {
-        constexpr int R = decltype(r_c)::value;  // slices after this one
-        slice(F_{}, F_{}, std::integral_constant<int, R - 1>{}, nk - 1 - R);
-        if constexpr (R > 0) self(self, std::integral_constant<int, R - 1>{});
-    };
-    tail(tail, std::integral_constant<int, STAGES - 2>{});
-    __syncthreads();  // every wavefront is done with the ring
-
-#pragma unroll
-    for (int t = 0; t < BPT; ++t) {
-        const int c = tid + t * 64 * NW;
-        if (c < BN) s_bias[c] = bias_reg[t];
-    }
-    if (kEpi == EPI_Q_TABLE) {
-#pragma unroll
-        for (int t = 0; t < KPT; ++t) {
-            const int e = tid + t * 64 * NW;
-            if (e < p.table.nseg) s_kb[e] = kb_reg[t];
-        }
-        for (int e = tid + KPT * 64 * NW; e < p.table.nseg; e += 64 * NW) s_kb[e] = p.table.kb[e];
-    }
-    constexpr int RW = BN + 16;  // row stride of the residual image
-    int8_t* s_res = smem;        // in the ring, which is free now
-    if (kEpi == EPI_F32_RESID) {
-#pragma unroll
-        for (int t = 0; t < RPT; ++t) {
-            const int c = tid + t * 64 * NW, row = c / CPRW, cc = c % CPRW;
-            if (c < BM * CPRW) *reinterpret_cast<v4i*>(s_res + row * RW + 16 * cc) = res_reg[t];
-        }
-    }
-    __syncthreads();
-
-    // ---- epilogue -----------------------------------------------------------------------------
-    const float alpha = p.alpha;
-    const bool full = m0 + BM <= p.M && n0 + BN <= p.N;
-    v4f bi[TN][4];
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) bi[j][g] = *reinterpret_cast<const v4f*>(s_bias + wave_n + 32 * j + 8 * g + 4 * frag_half);
-    constexpr int NG = TM * TN * 4;  // groups of four columns per lane
-    if (kEpi == EPI_Q_TABLE || kEpi == EPI_Q) {
-        constexpr int SW = WN + 16;
-        static_assert(NW * WM * SW <= STAGES * STAGE_BYTES, "patch fits the ring");
-        int8_t* patch = smem + wave * (WM * SW);
-        // inverse output scale of a group (the QKV projection has one per column third)
-        float inv_g[TN][4];
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wave_n + 32 * j + 8 * g + 4 * frag_half;
-                inv_g[j][g] = p.split_cols > 0 ? (n >= 2 * p.split_cols ? p.inv3[2] : n >= p.split_cols ? p.inv3[1] : p.inv3[0])
-                                               : p.out_inv_scale;
-            }
-        constexpr int DEPTH = 3;
-        float x[DEPTH + 1][4];
-        float2 kb[DEPTH + 1][4];
-        const float tlo = p.table.lo, tiw = p.table.inv_w, tmax = (float)(p.table.nseg - 1);
-        // group index -> (i, j, g), i innermost: consecutive groups use different accumulators
-        auto stage_a = [&](int G) {
-            const int i = G % TM, jg = G / TM, j = jg / 4, g = jg % 4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float v = __builtin_fmaf((float)acc[i][j][4 * g + e], alpha, bi[j][g][e]);
-                x[G % (DEPTH + 1)][e] = v;
-                if (kEpi == EPI_Q_TABLE) {  // segment of v (subtract, multiply, clamp in float, floor)
-                    float u = v - tlo;
-                    u = u * tiw;
-                    u = __builtin_amdgcn_fmed3f(u, 0.0f, tmax);
-                    kb[G % (DEPTH + 1)][e] = s_kb[(int)u];
-                }
-            }
-        };
-        auto stage_b = [&](int G) {
-            const int i = G % TM, jg = G / TM, j = jg / 4, g = jg % 4;
-            int q[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float v = x[G % (DEPTH + 1)][e];
-                if (kEpi == EPI_Q_TABLE) v = __builtin_fmaf(kb[G % (DEPTH + 1)][e].x, v, kb[G % (DEPTH + 1)][e].y);
-                q[e] = requant(v, inv_g[j][g]);
-            }
-            *reinterpret_cast<unsigned*>(patch + (32 * i + frag_row) * SW + 32 * j + 8 * g + 4 * frag_half) =
-                pack4(q[0], q[1], q[2], q[3]);
-        };
-#pragma unroll
-        for (int G = 0; G < NG + DEPTH; ++G) {
-            if (G < NG) stage_a(G);
-            __builtin_amdgcn_sched_barrier(0);
-            if (G >= DEPTH) stage_b(G - DEPTH);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // the wavefront reads back the rows it wrote: order its LDS writes before its reads
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        constexpr int PCPR = WN / 16;
-        constexpr int NCH = WM * PCPR / 64;  // 16-byte chunks per lane
-        static_assert(WM * PCPR % 64 == 0, "chunks split evenly");
-        v4i rows[NCH];
-#pragma unroll
-        for (int t = 0; t < NCH; ++t) {
-            const int c = lane + 64 * t, row = c / PCPR, cc = c % PCPR;
-            rows[t] = *reinterpret_cast<const v4i*>(patch + row * SW + 16 * cc);
-        }
-#pragma unroll
-        for (int t = 0; t < NCH; ++t) {
-            const int c = lane + 64 * t, row = c / PCPR, cc = c % PCPR;
-            const int mr = m0 + wave_m + row, n = n0 + wave_n + 16 * cc;
-            if (full || (mr < p.M && n < p.N)) *reinterpret_cast<v4i*>(p.out_q + (long)mr * p.ldo + n) = rows[t];
-        }
-    } else {
-        const float rs = p.resid_scale;
-#pragma unroll
-        for (int G = 0; G < NG; ++G) {
-            const int i = G % TM, jg = G / TM, j = jg / 4, g = jg % 4;
-            const int row = wave_m + 32 * i + frag_row, cl = wave_n + 32 * j + 8 * g + 4 * frag_half;
-            const unsigned rw = *reinterpret_cast<const unsigned*>(s_res + row * RW + cl);
-            v4f y;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float v = __builtin_fmaf((float)acc[i][j][4 * g + e], alpha, bi[j][g][e]);
-                y[e] = __builtin_fmaf((float)(int)(int8_t)(rw >> (8 * e)), rs, v);
-            }
-            const int m = m0 + row, n = n0 + cl;
-            if (full || (m < p.M && n < p.N)) *reinterpret_cast<v4f*>(p.out_f32 + (long)m * p.ldo + n) = y;
-        }
-    }
-}
-
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int kEpi>
-static int32_t launch_tile_epi(GemmParams& p, size_t table_bytes, hipStream_t s)
-{
-    auto kern = gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, kEpi>;
-    const size_t shmem = (size_t)STAGES * (BM + BN) * 128 + BN * sizeof(float) + table_bytes;
-    static std::once_flag once;  // one attribute call per instantiation
-    static int32_t once_rc = NM_OK;
-    std::call_once(once, [&] {
-        once_rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
-                            "hipFuncSetAttribute(gemm_tile_kernel)");
-    });
-    if (once_rc) return once_rc;
-    p.tiles_m = (p.M + BM - 1) / BM;
-    p.tiles_n = (p.N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n), dim3(64 * WAVES_M * WAVES_N), shmem, s, p);
-    return NM_OK;
-}
-
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
-static int32_t launch_tile(GemmParams& p, int epi, size_t table_bytes, hipStream_t s)
-{
-    switch (epi) {
-    case EPI_Q: return launch_tile_epi<BM, BN, WAVES_M, WAVES_N, STAGES, EPI_Q>(p, table_bytes, s);
-    case EPI_Q_TABLE: return launch_tile_epi<BM, BN, WAVES_M, WAVES_N, STAGES, EPI_Q_TABLE>(p, table_bytes, s);
-    default: return launch_tile_epi<BM, BN, WAVES_M, WAVES_N, STAGES, EPI_F32_RESID>(p, table_bytes, s);
-    }
-}
-
 template <int BM, int BN, int WM, int WN>
 static void launch_cfg(const GemmParams& p, bool al, bool wkn, dim3 grid, size_t shmem, hipStream_t s)
 {
@@ -1299,8 +886,36 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     const bool tile_ok = stream_ok && tile_epi && batches == 1 && g.K % 128 == 0 && g.K / 128 >= 3 && !g.alpha_vec &&
                          g.N % 16 == 0 && g.split_cols % 4 == 0 && (int64_t)g.M * g.lda < (1LL << 32) &&
                          (int64_t)g.N * g.ldw < (1LL << 32) && table_bytes <= 40 * 1024;
-    if (tile_ok && cfg == CFG_BIG && !old_big) {
+    // Which tile: the one whose workgroups fill whole rounds of the 256 CUs best, weighted by how much
+    // operand traffic per matrix instruction the tile shape costs (weights from timings of the
+    // encoder shapes: 256x192 1.0, 256x128 0.92, 128x192 0.85, 128x128 0.75) and by the share of the
+    // tiles' area that lies inside the output.
+    int tile_cfg = -1;
+    if (tile_ok && !old_big && forced_cfg() < 0) {
+        static const struct { int bm, bn, stages; double quality; } kTiles[4] = {
+            {256, 192, 2, 1.0}, {256, 128, 3, 0.92}, {128, 192, 3, 0.85}, {128, 128, 3, 0.75}};
+        double best = 0.0;
+        for (int c = 0; c < 4; ++c) {
+            if (g.K / 128 < kTiles[c].stages + 1) continue;
+            const long tm = (g.M + kTiles[c].bm - 1) / kTiles[c].bm, tn = (g.N + kTiles[c].bn - 1) / kTiles[c].bn;
+            const long tiles = tm * tn, slots = (tiles + 255) / 256 * 256;
+            const double inside = (double)g.M * g.N / ((double)tiles * kTiles[c].bm * kTiles[c].bn);
+            const double score = (double)tiles / (double)slots * inside * kTiles[c].quality;
+            if (score > best) { best = score; tile_cfg = c; }
+        }
+        // small problems stay with the streaming kernel's small tiles
+        if ((long)g.M * g.N < 128L * 128 * 96) tile_cfg = -1;
+    } else if (tile_ok && !old_big && forced_cfg() == 0 && g.K / 128 >= 3) {
+        tile_cfg = 0;
+    }
+    if (tile_cfg == 0) {
         rc = launch_tile<256, 192, 4, 2, 2>(p, epi, table_bytes, stream);
+    } else if (tile_cfg == 1) {
+        rc = launch_tile<256, 128, 4, 2, 3>(p, epi, table_bytes, stream);
+    } else if (tile_cfg == 2) {
+        rc = launch_tile<128, 192, 2, 2, 3>(p, epi, table_bytes, stream);
+    } else if (tile_cfg == 3) {
+        rc = launch_tile<128, 128, 2, 2, 3>(p, epi, table_bytes, stream);
     } else if (stream_ok && cfg == CFG_WIDE) {
         rc = launch_stream<256, 128, 2, 2, 1, 64, 2>(p, epi, batches, table_bytes, stream);
     } else if (stream_ok && cfg == CFG_BIG) {

@@ -407,6 +407,34 @@ def test_gemm_every_streaming_tile_configuration(oracle, M, N, K, what):
     assert_exact(host(oq), r3["q"], f"int8 + residual + table: {what}")
 
 
+@pytest.mark.parametrize("M,N,K,what", [
+    (3900, 2992, 384, "256x192 tiles, two stages, ragged edges"), (8192, 1024, 512, "256x128 tiles"),
+    (8192, 768, 512, "128x192 tiles"), (4096, 768, 512, "128x128 tiles"),
+    (4000, 720, 640, "128x128 tiles, ragged edges"), (4096, 3072, 768, "256x192 tiles, one per CU")])
+def test_gemm_tile_kernel_configurations(oracle, M, N, K, what):
+    """Shapes that reach each configuration of the large-tile kernel (aligned operands, K a multiple
+    of 128, scalar alpha): int8 output with and without the table, fp32 output with the residual."""
+    ot, dt = both_tables(oracle, [("gelu", -8.0, 8.0, 128)])
+    d = W.gemm_inputs(M, N, K, seed=K + N + 1, full_range=False)
+    alpha = float(np.float32(6.0 / (20 * 20 * np.sqrt(K))))
+    dA, dW, db, dr = dev(d["A"]), dev(d["W"]), dev(d["bias"]), dev(d["resid"])
+    oq = torch.full((M, N), 77, dtype=torch.int8, device=DEV)
+    r = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, table=ot[0], out_inv_scale=25.0)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, tables=dt, table_idx=0, out_inv_scale=25.0, out_q=oq)
+    assert_exact(host(oq), r["q"], f"int8 + table: {what}")
+    assert len(np.unique(r["seg"])) > 8
+    r1 = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, out_inv_scale=40.0)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, out_inv_scale=40.0, out_q=oq)
+    assert_exact(host(oq), r1["q"], f"int8: {what}")
+    nm.nm_gemm_pwl(dA, dW, alpha=alpha, out_inv_scale=40.0, out_q=oq)      # no bias vector
+    r1b = oracle.gemm_pwl(d["A"], d["W"], alpha=alpha, out_inv_scale=40.0)
+    assert_exact(host(oq), r1b["q"], f"int8, no bias: {what}")
+    r2 = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha, resid=d["resid"], resid_scale=0.02)
+    of = torch.full((M, N), -3.0, dtype=torch.float32, device=DEV)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, resid=dr, resid_scale=0.02, out_f32=of)
+    assert_f32_close(host(of), r2["y"], f"fp32 + residual: {what}")
+
+
 def test_gemm_extreme_operands(oracle):
     """All-(-127) x all-(+127) at the largest K of the workloads: |acc| = K * 127^2 > 2^24."""
     M, N, K = 40, 72, 3072
