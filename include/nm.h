@@ -148,6 +148,10 @@ void nm_tables_destroy(nm_tables* t);
  * required).  Limits: 1 <= M, N, K; K <= 65536 (so |acc| <= K * 127^2 < 2^31); M*N < 2^31.
  * Shapes whose K is a multiple of 16 with 16-byte aligned A and W take the fast loader; any
  * other shape is computed by a slower loader with identical results.
+ * Debug switches (environment, read once per process; results never change, only the kernel that
+ * computes them): NM_GEMM_GENERIC=1 sends every shape to the generic kernel; NM_GEMM_CFG=
+ * big|wide|split|small|mid3|mid2|oldbig forces a tile configuration where its requirements hold;
+ * NM_ATTN_UNFUSED=1 keeps nm_encoder_layer's attention on the three separate kernels.
  * --------------------------------------------------------------------------------------------- */
 typedef struct {
     int32_t M, N, K;
@@ -166,6 +170,11 @@ typedef struct {
     float* out_f32;
     int32_t* out_acc;
     uint16_t* dbg_seg;
+    /* split_cols > 0: the int8 code of column n uses out_inv_scale3[min(n / split_cols, 2)] instead of
+     * out_inv_scale (a fused Q | K | V projection has one output scale per third); out_inv_scale_vec
+     * must then be NULL.  0: not used. */
+    int32_t split_cols;
+    float out_inv_scale3[3];
 } nm_gemm_desc;
 
 int32_t nm_gemm_pwl(const nm_gemm_desc* desc, void* stream);

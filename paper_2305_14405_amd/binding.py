@@ -47,7 +47,8 @@ class GemmDesc(C.Structure):
                 ("alpha", C.c_float), ("resid", C.c_void_p), ("resid_scale", C.c_float),
                 ("tables", C.c_void_p), ("table_idx", C.c_int32), ("out_inv_scale", C.c_float),
                 ("out_inv_scale_vec", C.c_void_p), ("out_q", C.c_void_p), ("out_f32", C.c_void_p),
-                ("out_acc", C.c_void_p), ("dbg_seg", C.c_void_p)]
+                ("out_acc", C.c_void_p), ("dbg_seg", C.c_void_p), ("split_cols", C.c_int32),
+                ("out_inv_scale3", C.c_float * 3)]
 
 
 class ConvDesc(C.Structure):
@@ -260,7 +261,7 @@ def nm_tables_get(t: Tables, idx: int):
 def nm_gemm_pwl(A, W, *, bias=None, alpha=1.0, alpha_vec=None, resid=None, resid_scale=0.0,
                 tables: Tables | None = None, table_idx=-1, out_inv_scale=1.0,
                 out_inv_scale_vec=None, out_q=None, out_f32=None, out_acc=None, dbg_seg=None,
-                stream=None, M=None, N=None, K=None):
+                stream=None, M=None, N=None, K=None, split_cols=0, out_inv_scale3=None):
     d = GemmDesc()
     d.M = A.shape[0] if M is None else M
     d.K = A.shape[1] if K is None else K
@@ -273,6 +274,9 @@ def nm_gemm_pwl(A, W, *, bias=None, alpha=1.0, alpha_vec=None, resid=None, resid
     d.out_inv_scale = out_inv_scale
     d.out_inv_scale_vec = _ptr(out_inv_scale_vec)
     d.out_q, d.out_f32, d.out_acc, d.dbg_seg = _ptr(out_q), _ptr(out_f32), _ptr(out_acc), _ptr(dbg_seg)
+    d.split_cols = split_cols
+    if out_inv_scale3 is not None:
+        d.out_inv_scale3 = (C.c_float * 3)(*[float(v) for v in out_inv_scale3])
     _check(load().nm_gemm_pwl(C.byref(d), _stream(stream)))
 
 

@@ -956,6 +956,8 @@ int32_t nm_gemm_pwl(const nm_gemm_desc* d, void* stream)
     if (!d->out_q && !d->out_f32 && !d->out_acc) return fail(NM_ERR_INVALID_ARG, "nm_gemm_pwl: no output");
     if (d->K > 65536) return fail(NM_ERR_UNSUPPORTED, "nm_gemm_pwl: K %d > 65536", d->K);
     if ((int64_t)d->M * d->N >= (1LL << 31)) return fail(NM_ERR_UNSUPPORTED, "nm_gemm_pwl: M*N >= 2^31");
+    if (d->split_cols < 0 || (d->split_cols > 0 && d->out_inv_scale_vec))
+        return fail(NM_ERR_INVALID_ARG, "nm_gemm_pwl: split_cols must be >= 0 and excludes out_inv_scale_vec");
     GemmArgs g;
     g.M = d->M; g.N = d->N; g.K = d->K;
     g.A = d->A; g.lda = d->K; g.W = d->W; g.ldw = d->K;
@@ -967,6 +969,8 @@ int32_t nm_gemm_pwl(const nm_gemm_desc* d, void* stream)
         g.has_table = 1;
     }
     g.out_inv_scale = d->out_inv_scale; g.out_inv_scale_vec = d->out_inv_scale_vec;
+    g.split_cols = d->split_cols;
+    for (int i = 0; i < 3; ++i) g.inv3[i] = d->out_inv_scale3[i];
     g.ldo = d->N;
     g.out_q = d->out_q; g.out_f32 = d->out_f32; g.out_acc = d->out_acc; g.dbg_seg = d->dbg_seg;
     return launch_gemm(g, (hipStream_t)stream);
