@@ -2,6 +2,7 @@
 // launches on one stream (paper Section 3: linear operators as matrix products, nonlinear
 // operators as PWL tables).  Host code only: it validates, carves the workspace and queues the
 // nine steps; nothing is allocated and the host never waits for the GPU.
+#include <cmath>
 #include <cstdlib>
 #include <mutex>
 
@@ -50,7 +51,7 @@ static LayerPlan plan_layer(const nm_layer_desc* d)
     return p;
 }
 
-static int32_t validate_layer(const nm_layer_desc* d, const char* what)
+static int32_t validate_layer(const nm_layer_desc* d, const char* what, bool numbers = false)
 {
     if (!d) return fail(NM_ERR_INVALID_ARG, "%s: desc is NULL", what);
     if (d->B < 1 || d->S < 1 || d->H < 1 || d->heads < 1 || d->F < 1)
@@ -64,6 +65,15 @@ static int32_t validate_layer(const nm_layer_desc* d, const char* what)
     const int64_t M = (int64_t)d->B * d->S;
     if (M * 3 * d->H >= (1LL << 31) || M * d->F >= (1LL << 31))
         return fail(NM_ERR_UNSUPPORTED, "%s: B*S*max(3H, F) >= 2^31", what);
+    if (!numbers) return NM_OK;  // a workspace query has dimensions only
+    // every multiplier must be finite (a NaN or infinity would reach the table look-ups, whose
+    // kernels assume finite inputs); the score scale is a positive number by its definition
+    const float mult[] = {d->alpha_qkv, d->inv_s_q, d->inv_s_k, d->inv_s_v, d->alpha_scores, d->inv_s_p,
+                          d->alpha_ctx, d->inv_s_ctx, d->alpha_o, d->resid1_scale, d->inv_s_ln1, d->alpha_1,
+                          d->inv_s_ffn1, d->alpha_2, d->resid2_scale, d->inv_s_out, d->eps1, d->eps2};
+    for (float v : mult)
+        if (!std::isfinite(v)) return fail(NM_ERR_INVALID_ARG, "%s: a scale / multiplier is not finite", what);
+    if (!(d->alpha_scores > 0.0f)) return fail(NM_ERR_INVALID_ARG, "%s: alpha_scores must be > 0", what);
     return NM_OK;
 }
 
@@ -115,7 +125,7 @@ int32_t nm_encoder_layer_workspace(const nm_layer_desc* desc, size_t* bytes)
 int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, float* y_f32,
                          void* ws, size_t ws_bytes, const nm_layer_taps* taps, void* stream_)
 {
-    int32_t rc = validate_layer(d, "nm_encoder_layer");
+    int32_t rc = validate_layer(d, "nm_encoder_layer", true);
     if (rc) return rc;
     if (!x) return fail(NM_ERR_INVALID_ARG, "nm_encoder_layer: x is NULL");
     if (!y_q && !y_f32) return fail(NM_ERR_INVALID_ARG, "nm_encoder_layer: no output");
@@ -221,7 +231,7 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
 
 int32_t nm_encoder_layer_noalloc(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, float* y_f32, void* stream)
 {
-    int32_t rc = validate_layer(d, "nm_encoder_layer_noalloc");
+    int32_t rc = validate_layer(d, "nm_encoder_layer_noalloc");  // dimensions; nm_encoder_layer checks the rest
     if (rc) return rc;
     const size_t need = plan_layer(d).total;
     if (need > kStaticScratchBytes)

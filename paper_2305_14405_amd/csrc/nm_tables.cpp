@@ -115,12 +115,18 @@ static Line fit_segment(int func, double a, double c, bool correct, double e_th)
 static int32_t validate_desc(const nm_table_desc* d, bool need_func)
 {
     if (!d) return fail(NM_ERR_INVALID_ARG, "table descriptor is NULL");
-    if (!(d->hi > d->lo)) return fail(NM_ERR_INVALID_ARG, "table range needs hi > lo");
+    if (!(d->hi > d->lo) || !std::isfinite(d->lo) || !std::isfinite(d->hi))
+        return fail(NM_ERR_INVALID_ARG, "table range needs finite lo < hi");
     if (d->nseg < 1) return fail(NM_ERR_INVALID_ARG, "table needs nseg >= 1 (got %d)", d->nseg);
     if (d->nseg > NM_MAX_SEGMENTS)
         return fail(NM_ERR_UNSUPPORTED, "nseg %d exceeds NM_MAX_SEGMENTS %d", d->nseg,
                     NM_MAX_SEGMENTS);
     if (need_func) {
+        // thresholds of Algorithm 3 / Algorithm 2: finite and not negative
+        if ((d->flags & NM_TABLE_BIAS_CORRECT) && !(d->e_th >= 0.0f && std::isfinite(d->e_th)))
+            return fail(NM_ERR_INVALID_ARG, "e_th must be finite and >= 0");
+        if ((d->flags & NM_TABLE_MERGE) && !(d->dk_th >= 0.0f && std::isfinite(d->dk_th)))
+            return fail(NM_ERR_INVALID_ARG, "dk_th must be finite and >= 0");
         double y;
         if (!eval_f(d->func, 1.0, &y))
             return fail(NM_ERR_INVALID_ARG, "unknown function id %d", d->func);

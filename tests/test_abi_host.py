@@ -137,6 +137,17 @@ def test_compute_entry_points_validate_before_launch(lib):
     need2 = M2 * 3 * 128 + SS2 * 4 + SS2 + M2 * 128 + M2 * 128 * 4 + M2 * 128 + M2 * 256 + M2 * 128 * 4
     assert need2 <= n2.value <= need2 + 8 * 256
     assert lib.nm_encoder_layer(C.byref(ld), one, one, None, one, n, None, z) == nm.NM_ERR_INVALID_ARG
+    # scales and multipliers are checked before any GPU call: finite, score scale positive
+    for name in nm.LAYER_FLOATS:
+        setattr(ld, name, 1.0)
+    ld.eps1 = ld.eps2 = 1e-5
+    for name, bad in (("alpha_scores", float("inf")), ("alpha_scores", 0.0), ("alpha_1", float("nan")),
+                      ("inv_s_out", float("-inf")), ("eps2", float("nan"))):
+        keep = getattr(ld, name)
+        setattr(ld, name, bad)
+        assert lib.nm_encoder_layer(C.byref(ld), one, one, None, one, n, None, z) == nm.NM_ERR_INVALID_ARG
+        assert b"multiplier" in lib.nm_last_error() or b"alpha_scores" in lib.nm_last_error()
+        setattr(ld, name, keep)
     # the entry point that allocates nothing: validation and the size limit come before any GPU call
     assert lib.nm_encoder_layer_noalloc(None, one, one, None, z) == nm.NM_ERR_INVALID_ARG
     ld3 = nm.LayerDesc()
