@@ -62,9 +62,16 @@ enum { NM_FUNC_GELU = 0, NM_FUNC_EXP = 1, NM_FUNC_RECIP = 2, NM_FUNC_RSQRT = 3, 
 enum {
     NM_TABLE_CLAMP_INPUT = 1,  /* clamp x to [lo, hi] before evaluation instead of extrapolating */
     NM_TABLE_BIAS_CORRECT = 2, /* Algorithm 3: shift b by the expectation bias when |dE| > e_th */
-    NM_TABLE_MERGE = 4         /* Algorithm 2: merge neighbouring primary segments whose slope
+    NM_TABLE_MERGE = 4,        /* Algorithm 2: merge neighbouring primary segments whose slope
                                   stays within dk_th of the slope at the last kept start point;
                                   nseg is then the number of primary cells */
+    NM_TABLE_COMPACT = 8       /* keep a merged table in two levels as well: one {k, b} per merged
+                                  segment plus one byte per primary cell naming its segment (at most
+                                  256 segments), so that a kernel holds n_segments * 8 + nseg bytes of
+                                  it instead of nseg * 8.  nm_pwl_apply and nm_gemm_pwl look such a
+                                  table up in two steps (cell of x, segment of the cell); the other
+                                  entry points use its expanded form.  Results are identical either
+                                  way; reported segment indices are always primary cell indices */
 };
 
 enum { NM_DT_I32 = 0, NM_DT_F32 = 1 };
@@ -113,7 +120,8 @@ int32_t nm_build_tables(const nm_table_desc* descs, int32_t n, void* stream, nm_
 
 /*
  * Same, but k and b come from the caller: k[i], b[i] are host arrays of descs[i].nseg floats.
- * descs[i].func / e_th / dk_th are ignored, lo / hi / nseg / NM_TABLE_CLAMP_INPUT are used.
+ * descs[i].func / e_th / dk_th are ignored, lo / hi / nseg / NM_TABLE_CLAMP_INPUT /
+ * NM_TABLE_COMPACT are used (the two-level form is derived from runs of equal {k, b}).
  */
 int32_t nm_tables_from_arrays(const nm_table_desc* descs, int32_t n, const float* const* k,
                               const float* const* b, void* stream, nm_tables** out);
@@ -127,6 +135,14 @@ int32_t nm_tables_count(const nm_tables* t);
  */
 int32_t nm_tables_get(const nm_tables* t, int32_t idx, nm_table_desc* desc, float* k_host,
                       float* b_host, float* inv_w);
+
+/*
+ * The two-level form of table idx (built with NM_TABLE_COMPACT): number of merged segments, the
+ * segment of every primary cell (host array of nseg bytes), and the segments' parameters (host
+ * arrays of *n_segments floats; query the count first).  Any output may be NULL.
+ */
+int32_t nm_tables_get_compact(const nm_tables* t, int32_t idx, int32_t* n_segments, uint8_t* cell_to_segment,
+                              float* k_host, float* b_host);
 
 /* Frees the host copy and the device blob.  NULL is allowed.  The caller must make sure no kernel
  * that uses the tables is still running. */

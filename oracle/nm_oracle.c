@@ -323,6 +323,86 @@ int nmo_pwl_apply(const void* in, int32_t in_dtype, float alpha, int64_t n, cons
 }
 
 /* ------------------------------------------------------------------------------------------- */
+/* A merged table in its own form (Algorithm 2's output), evaluated directly.                   */
+/* ------------------------------------------------------------------------------------------- */
+
+/*
+ * Algorithm 2 returns start points, all of them multiples of the primary length dLx from r_min;
+ * merged segment i covers [x_i, x_{i+1}) and has one line (Algorithm 3).  Here the start points are
+ * kept as primary-cell numbers (x_i = lo + start_cell[i] * dLx, start_cell[0] = 0, increasing).
+ */
+typedef struct {
+    float lo, hi;
+    float inv_w;            /* (float)(nprimary / (hi - lo)) */
+    int32_t nprimary;       /* primary cells of length dLx */
+    int32_t flags;          /* NMO_FLAG_CLAMP_INPUT */
+    int32_t nseg;           /* merged segments */
+    const int32_t* start_cell; /* [nseg] */
+    const float* k;         /* [nseg] */
+    const float* b;         /* [nseg] */
+} nmo_merged_table;
+
+/* Start cells and one chord per merged segment (no expansion onto the primary grid). */
+int nmo_table_build_merged_direct(int32_t func, float lo, float hi, int32_t nprimary, double dk_th,
+                                  int32_t flags, double e_th, int32_t* start_cell, float* k, float* b,
+                                  float* inv_w, int32_t* n_merged)
+{
+    nmo_fn f = fn_of(func), F = antiderivative_of(func);
+    if (!f || !start_cell || !k || !b || !inv_w || !n_merged || nprimary < 1 || !(hi > lo)) return NMO_ERR_ARG;
+    double L = (double)lo, R = (double)hi;
+    double w = (R - L) / (double)nprimary;
+    double* xs = (double*)malloc(sizeof(double) * (size_t)(nprimary + 1));
+    if (!xs) return NMO_ERR_ALLOC;
+    int32_t n = nmo_size_optimize(f, L, R, w, dk_th, xs, nprimary);
+    if (n < 1) { free(xs); return NMO_ERR_ARG; }
+    xs[n] = R;
+    for (int32_t i = 0; i < n; ++i) {
+        double kk, bb;
+        chord_segment(f, F, xs[i], xs[i + 1], (flags & NMO_FLAG_BIAS_CORRECT) != 0, e_th, &kk, &bb);
+        k[i] = (float)kk;
+        b[i] = (float)bb;
+        start_cell[i] = (int32_t)llround((xs[i] - L) / w);
+    }
+    *inv_w = (float)((double)nprimary / (R - L));
+    *n_merged = n;
+    free(xs);
+    return NMO_OK;
+}
+
+/*
+ * Evaluation: x is quantised to its primary cell exactly as for a uniform table (one subtract, one
+ * multiply, clamp in float, floor: inputs outside the range fall into the edge cells and so share
+ * the edge segments' parameters), then the merged segment is the one whose start point is the last
+ * at or below that cell (binary search over the start points), then y = fma(k, x, b).
+ */
+int nmo_pwl_apply_merged(const void* in, int32_t in_dtype, float alpha, int64_t n,
+                         const nmo_merged_table* t, float out_inv_scale, int8_t* out_q, float* out_f32,
+                         uint16_t* dbg_seg, uint16_t* dbg_cell)
+{
+    if (!in || !t || n < 0 || t->nseg < 1 || t->start_cell[0] != 0) return NMO_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        float x = (in_dtype == NMO_DT_I32) ? (float)((const int32_t*)in)[i] * alpha
+                                           : ((const float*)in)[i] * alpha;
+        if (t->flags & NMO_FLAG_CLAMP_INPUT) x = fminf(fmaxf(x, t->lo), t->hi);
+        float u = x - t->lo;
+        u = u * t->inv_w;
+        u = fminf(fmaxf(u, 0.0f), (float)(t->nprimary - 1));
+        int32_t cell = (int32_t)floorf(u);
+        int32_t lo_i = 0, hi_i = t->nseg - 1;      /* last start point <= cell */
+        while (lo_i < hi_i) {
+            int32_t mid = (lo_i + hi_i + 1) / 2;
+            if (t->start_cell[mid] <= cell) lo_i = mid; else hi_i = mid - 1;
+        }
+        float y = fmaf(t->k[lo_i], x, t->b[lo_i]);
+        if (out_f32) out_f32[i] = y;
+        if (out_q) out_q[i] = requant(y, out_inv_scale);
+        if (dbg_seg) dbg_seg[i] = (uint16_t)lo_i;
+        if (dbg_cell) dbg_cell[i] = (uint16_t)cell;
+    }
+    return NMO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------- */
 /* Canonical row reduction.                                                                     */
 /* ------------------------------------------------------------------------------------------- */
 

@@ -199,6 +199,70 @@ def build_table_merged(func: int, lo: float, hi: float, nprimary: int, dk_th: fl
     return Table(lo, hi, nprimary, k, b, inv_w[0], flags, func), int(nm[0])
 
 
+class MergedTable:
+    """A merged table in its own form: start cells (multiples of the primary length from lo) and one
+    line per merged segment."""
+
+    def __init__(self, lo, hi, nprimary, start_cell, k, b, inv_w, flags=0):
+        self.lo, self.hi, self.nprimary = float(lo), float(hi), int(nprimary)
+        self.start_cell = np.ascontiguousarray(start_cell, np.int32)
+        self.k = np.ascontiguousarray(k, np.float32)
+        self.b = np.ascontiguousarray(b, np.float32)
+        self.inv_w, self.flags = np.float32(inv_w), int(flags)
+
+    @property
+    def nseg(self):
+        return int(self.k.size)
+
+    def cell_to_segment(self):
+        """Merged segment of every primary cell."""
+        return (np.searchsorted(self.start_cell, np.arange(self.nprimary), side="right") - 1).astype(np.uint8)
+
+    def ref(self):
+        class _S(C.Structure):
+            _fields_ = [("lo", C.c_float), ("hi", C.c_float), ("inv_w", C.c_float), ("nprimary", C.c_int32),
+                        ("flags", C.c_int32), ("nseg", C.c_int32), ("start_cell", C.c_void_p),
+                        ("k", C.c_void_p), ("b", C.c_void_p)]
+        self._struct = _S(self.lo, self.hi, float(self.inv_w), self.nprimary, self.flags & FLAG_CLAMP_INPUT, self.nseg,
+                          self.start_cell.ctypes.data, self.k.ctypes.data, self.b.ctypes.data)
+        return C.byref(self._struct)
+
+
+def build_table_merged_direct(func: int, lo: float, hi: float, nprimary: int, dk_th: float,
+                              flags: int = 0, e_th: float = 0.0) -> MergedTable:
+    """Algorithm 2 + Algorithm 3 without expansion: start cells and one line per merged segment."""
+    start = np.zeros(nprimary, np.int32)
+    k = np.zeros(nprimary, np.float32)
+    b = np.zeros(nprimary, np.float32)
+    inv_w = np.zeros(1, np.float32)
+    n = np.zeros(1, np.int32)
+    fn = lib().nmo_table_build_merged_direct
+    fn.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_double, C.c_int32, C.c_double,
+                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(fn(func, lo, hi, nprimary, dk_th, flags, e_th, _p(start), _p(k), _p(b), _p(inv_w), _p(n)),
+           "table_build_merged_direct")
+    m = int(n[0])
+    return MergedTable(lo, hi, nprimary, start[:m].copy(), k[:m].copy(), b[:m].copy(), inv_w[0], flags)
+
+
+def pwl_apply_merged(x, t: MergedTable, alpha: float = 1.0, out_inv_scale: float = 1.0):
+    """Direct evaluation of a merged table.  Returns (y, q, merged segment, primary cell)."""
+    x = np.ascontiguousarray(x)
+    dt = DT_I32 if x.dtype == np.int32 else DT_F32
+    if dt == DT_F32:
+        x = x.astype(np.float32)
+    n = x.size
+    y = np.empty(n, np.float32)
+    q = np.empty(n, np.int8)
+    s = np.empty(n, np.uint16)
+    c = np.empty(n, np.uint16)
+    fn = lib().nmo_pwl_apply_merged
+    fn.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_int64, C.c_void_p, C.c_float, C.c_void_p,
+                   C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(fn(_p(x), dt, alpha, n, t.ref(), out_inv_scale, _p(q), _p(y), _p(s), _p(c)), "pwl_apply_merged")
+    return y, q, s, c
+
+
 def size_optimize(func_or_callable, r_min, r_max, dlx, dk_th):
     cap = int(round((r_max - r_min) / dlx)) + 1
     xs = np.empty(cap, np.float64)

@@ -15,12 +15,12 @@ LIB_PATH = os.path.join(HERE, "libnm_hip.so")
 NM_OK = 0
 NM_ERR_INVALID_ARG, NM_ERR_UNSUPPORTED, NM_ERR_ALLOC, NM_ERR_HIP, NM_ERR_WORKSPACE = -1, -2, -3, -4, -5
 FUNC = {"gelu": 0, "exp": 1, "recip": 2, "rsqrt": 3, "relu": 4, "sqrt": 5, "identity": 6}
-NM_TABLE_CLAMP_INPUT, NM_TABLE_BIAS_CORRECT, NM_TABLE_MERGE = 1, 2, 4
+NM_TABLE_CLAMP_INPUT, NM_TABLE_BIAS_CORRECT, NM_TABLE_MERGE, NM_TABLE_COMPACT = 1, 2, 4, 8
 NM_DT_I32, NM_DT_F32 = 0, 1
 
 # every symbol include/nm.h declares
 EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_tables",
-           "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_destroy",
+           "nm_tables_from_arrays", "nm_tables_count", "nm_tables_get", "nm_tables_get_compact", "nm_tables_destroy",
            "nm_gemm_pwl", "nm_softmax_pwl", "nm_layernorm_pwl", "nm_layernorm_pwl2", "nm_pwl_apply", "nm_attn_scores",
            "nm_attn_context", "nm_attention_pwl", "nm_encoder_layer_workspace", "nm_encoder_layer",
            "nm_encoder_layer_noalloc",
@@ -116,6 +116,7 @@ def load(preload_torch: bool = True) -> C.CDLL:
     L.nm_tables_count.argtypes = [C.c_void_p]
     L.nm_tables_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(TableDesc), C.c_void_p,
                                 C.c_void_p, C.c_void_p]
+    L.nm_tables_get_compact.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.nm_tables_destroy.argtypes = [C.c_void_p]
     L.nm_tables_destroy.restype = None
     L.nm_gemm_pwl.argtypes = [C.POINTER(GemmDesc), C.c_void_p]
@@ -256,6 +257,20 @@ def nm_tables_get(t: Tables, idx: int):
     _check(load().nm_tables_get(t.handle, idx, None, k.ctypes.data, b.ctypes.data,
                                 inv_w.ctypes.data))
     return d, k, b, inv_w[0]
+
+
+def nm_tables_get_compact(t: Tables, idx: int):
+    """Two-level form of a table built with NM_TABLE_COMPACT: (cell_to_segment uint8 [nseg], k, b)."""
+    import numpy as np
+    d = TableDesc()
+    _check(load().nm_tables_get(t.handle, idx, C.byref(d), None, None, None))
+    n = C.c_int32()
+    _check(load().nm_tables_get_compact(t.handle, idx, C.byref(n), None, None, None))
+    cmap = np.zeros(d.nseg, np.uint8)
+    k = np.zeros(n.value, np.float32)
+    b = np.zeros(n.value, np.float32)
+    _check(load().nm_tables_get_compact(t.handle, idx, None, cmap.ctypes.data, k.ctypes.data, b.ctypes.data))
+    return cmap, k, b
 
 
 def nm_gemm_pwl(A, W, *, bias=None, alpha=1.0, alpha_vec=None, resid=None, resid_scale=0.0,

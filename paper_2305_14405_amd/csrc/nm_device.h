@@ -90,6 +90,29 @@ __device__ __forceinline__ void stage_table(float2* dst, const DevTable& t)
     for (int i = threadIdx.x; i < t.nseg; i += blockDim.x) dst[i] = t.kb[i];
 }
 
+// Two-level form of a merged table (paper Algorithm 2: neighbouring primary segments with nearly
+// equal slope share one line): nkb {k, b} pairs, then one byte per primary cell naming its merged
+// segment.  LDS bytes: 8 * nkb + nseg (instead of 8 * nseg).
+__device__ __forceinline__ size_t two_level_bytes(const DevTable& t) { return 8 * (size_t)t.nkb + (((size_t)t.nseg + 7) & ~(size_t)7); }
+__device__ __forceinline__ void stage_table_two_level(float2* dst, const DevTable& t)
+{
+    for (int i = threadIdx.x; i < t.nkb; i += blockDim.x) dst[i] = t.ckb[i];
+    uint8_t* map = reinterpret_cast<uint8_t*>(dst + t.nkb);
+    for (int i = threadIdx.x; i < t.nseg; i += blockDim.x) map[i] = t.cellmap[i];
+}
+
+// Look-up in two steps: the primary cell of x exactly as for a uniform table (`cell` is what the
+// debug outputs report), then that cell's merged segment.
+__device__ __forceinline__ float pwl_eval_two_level(float x, const DevTable& t, const float2* staged, int& cell)
+{
+    const float xc = __builtin_amdgcn_fmed3f(x, t.lo, t.hi);
+    x = t.clamp_input ? xc : x;
+    cell = seg_index(x, t.lo, t.inv_w, t.nseg);
+    const uint8_t* map = reinterpret_cast<const uint8_t*>(staged + t.nkb);
+    const float2 e = staged[map[cell]];
+    return __builtin_fmaf(e.x, x, e.y);
+}
+
 // Direct global -> LDS load: every lane supplies its own global address of 16 bytes; the wavefront's
 // 1 KB lands contiguously at lds_addr (wave-uniform), lane i at lds_addr + 16*i.  Asynchronous:
 // completion is tracked by the vector-memory counter (wait_vmcnt), not by the LDS counter.

@@ -160,7 +160,11 @@ __device__ __forceinline__ void epi_math(const GemmParams& p, const float2* s_kb
     for (int e = 0; e < 4; ++e) {
         float v = __builtin_fmaf((float)a4[e], c.scale[e], c.bias[e]);
         if (use_resid) v = __builtin_fmaf((float)r4[e], rs, v);
-        if (use_table) v = (kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID) ? pwl_eval_noclamp(v, p.table, s_kb, o.s[e]) : pwl_eval(v, p.table, s_kb, o.s[e]);
+        if (use_table) {
+            if (kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID) v = pwl_eval_noclamp(v, p.table, s_kb, o.s[e]);
+            else if (p.table.cellmap) v = pwl_eval_two_level(v, p.table, s_kb, o.s[e]);  // merged table, two steps
+            else v = pwl_eval(v, p.table, s_kb, o.s[e]);
+        }
         o.y[e] = v;
         if (need_q) o.q[e] = requant(v, c.inv[e]);
     }
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_pwl_kernel(GemmParams p)
     const int8_t* __restrict__ W = p.W + outer * p.w_outer + inner * p.w_inner;
     const long obase = outer * p.o_outer + inner * p.o_inner;
 
-    if (p.has_table) stage_table(s_kb, p.table);
+    if (p.has_table) { if (p.table.cellmap) stage_table_two_level(s_kb, p.table); else stage_table(s_kb, p.table); }
 
     v16i acc[TM][TN];
 #pragma unroll
@@ -428,7 +432,7 @@ void gemm_stream_kernel(GemmParams p)
     const int8_t* __restrict__ W = p.W + outer * p.w_outer + inner * p.w_inner;
     const long obase = outer * p.o_outer + inner * p.o_inner;
 
-    if (p.has_table) stage_table(s_kb, p.table);
+    if (p.has_table) { if (p.table.cellmap) stage_table_two_level(s_kb, p.table); else stage_table(s_kb, p.table); }
     // per-column epilogue parameters of this tile go to LDS now (their latency hides behind the
     // main loop) so that the epilogue itself issues no global loads for them
     if (kEpi != EPI_ACC) {
@@ -814,14 +818,18 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     p.r16 = g.resid && aligned(g.resid, 16) && g.ldo % 16 == 0 && g.o_outer % 16 == 0 && g.o_inner % 16 == 0 && g.N % 16 == 0;
     p.q16 = g.out_q && aligned(g.out_q, 16) && g.ldo % 16 == 0 && g.o_outer % 16 == 0 && g.o_inner % 16 == 0;
 
-    const size_t table_bytes = g.has_table ? sizeof(float2) * (size_t)g.table.nseg : 0;
+    // LDS bytes of the table: {k, b} per segment, or for the two-level form of a merged table one
+    // {k, b} per merged segment plus a byte per primary cell
+    const size_t table_bytes = !g.has_table ? 0
+                             : g.table.cellmap ? 8 * (size_t)g.table.nkb + (((size_t)g.table.nseg + 7) & ~(size_t)7)
+                                               : sizeof(float2) * (size_t)g.table.nseg;
     const int batches = g.outer_count * g.inner_count;
     if (batches > 65535) return fail(NM_ERR_UNSUPPORTED, "gemm: more than 65535 batched problems");
     int32_t rc = NM_OK;
     p.vec_cols = (!g.bias || aligned(g.bias, 16)) && (!g.alpha_vec || aligned(g.alpha_vec, 16)) &&
                  (!g.out_inv_scale_vec || aligned(g.out_inv_scale_vec, 16));
     int epi = EPI_GENERIC;
-    if (!g.out_inv_scale_vec && !g.dbg_seg) {
+    if (!g.out_inv_scale_vec && !g.dbg_seg && !(g.has_table && g.table.cellmap)) {
         const bool only_q = g.out_q && !g.out_f32 && !g.out_acc;
         // EPI_Q_TABLE is compiled without the input clamp; a table with that flag takes the generic epilogue
         if (only_q && !g.resid) epi = !g.has_table ? EPI_Q : g.table.clamp_input ? EPI_GENERIC : EPI_Q_TABLE;
@@ -964,7 +972,7 @@ int32_t nm_gemm_pwl(const nm_gemm_desc* d, void* stream)
     g.bias = d->bias; g.alpha_vec = d->alpha_vec; g.alpha = d->alpha;
     g.resid = d->resid; g.resid_scale = d->resid_scale;
     if (d->table_idx >= 0) {
-        int32_t rc = get_dev_table(d->tables, d->table_idx, &g.table, "nm_gemm_pwl");
+        int32_t rc = get_dev_table(d->tables, d->table_idx, &g.table, "nm_gemm_pwl", true);
         if (rc) return rc;
         g.has_table = 1;
     }

@@ -18,6 +18,11 @@ struct DevTable {
     float lo, hi, inv_w;
     int nseg;
     int clamp_input;
+    // two-level form of a merged table (NM_TABLE_COMPACT), null / 0 otherwise: cellmap[cell] is
+    // the merged segment of a primary cell, ckb[segment] its {k, b}; nkb segments
+    const float2* ckb;
+    const uint8_t* cellmap;
+    int nkb;
 };
 
 struct HostTable {
@@ -26,6 +31,11 @@ struct HostTable {
     int n_distinct;
     std::vector<float> k, b;
     size_t blob_offset;  // in float2 units
+    // two-level form (NM_TABLE_COMPACT): one {k, b} per merged segment and a byte per primary cell
+    std::vector<float> ck, cb;
+    std::vector<uint8_t> cellmap;
+    size_t cblob_offset = 0;  // float2 units
+    size_t map_offset = 0;    // float2 units (the map's bytes start there)
 };
 
 int32_t launch_layernorm2(const float* in, const float* gamma, const float* beta, float eps,
@@ -48,7 +58,9 @@ int32_t fail(int32_t code, const char* fmt, ...);
 int32_t check_hip(hipError_t e, const char* what);
 
 // Validates idx and fills dt.  Returns NM_OK or an error (message set).
-int32_t get_dev_table(const nm_tables* t, int32_t idx, DevTable* dt, const char* what);
+// two_level: also hand out the two-level form of a table built with NM_TABLE_COMPACT (only kernels
+// that look tables up in two steps ask for it; everything else works on the expanded form).
+int32_t get_dev_table(const nm_tables* t, int32_t idx, DevTable* dt, const char* what, bool two_level = false);
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

@@ -76,14 +76,16 @@ __device__ __forceinline__ float group_sum(float v)
 // ------------------------------------------------------------------------------------------
 // Stand-alone element-wise PWL (the non-fused element-wise path).
 // ------------------------------------------------------------------------------------------
-template <bool kVec>
+// kTwo: the table is in its two-level form (merged segments + cell map).
+template <bool kVec, bool kTwo = false>
 __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
     const void* __restrict__ in, int in_is_i32, float alpha, long n, DevTable t,
     float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
     uint16_t* __restrict__ dbg_seg)
 {
     extern __shared__ float2 s_kb[];
-    stage_table(s_kb, t);
+    if (kTwo) stage_table_two_level(s_kb, t);
+    else stage_table(s_kb, t);
     __syncthreads();
     const long nthreads = (long)gridDim.x * blockDim.x;
     const long tid = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
             int s[4], q[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                y[e] = pwl_eval(x[e], t, s_kb, s[e]);
+                y[e] = kTwo ? pwl_eval_two_level(x[e], t, s_kb, s[e]) : pwl_eval(x[e], t, s_kb, s[e]);
                 q[e] = requant(y[e], out_inv_scale);
             }
             if (out_f32) reinterpret_cast<v4f*>(out_f32)[gidx] = v4f{y[0], y[1], y[2], y[3]};
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
         float x = in_is_i32 ? (float)reinterpret_cast<const int*>(in)[i] * alpha
                             : reinterpret_cast<const float*>(in)[i] * alpha;
         int s;
-        float y = pwl_eval(x, t, s_kb, s);
+        float y = kTwo ? pwl_eval_two_level(x, t, s_kb, s) : pwl_eval(x, t, s_kb, s);
         if (out_f32) out_f32[i] = y;
         if (out_q) out_q[i] = (int8_t)requant(y, out_inv_scale);
         if (dbg_seg) dbg_seg[i] = (uint16_t)s;
@@ -525,23 +527,24 @@ int32_t nm_pwl_apply(const void* in, int32_t in_dtype, float alpha, int64_t n,
         return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: bad in_dtype %d", in_dtype);
     if (n < 0) return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: n < 0");
     DevTable t;
-    int32_t rc = get_dev_table(tables, idx, &t, "nm_pwl_apply");
+    int32_t rc = get_dev_table(tables, idx, &t, "nm_pwl_apply", true);
     if (rc) return rc;
     if (n == 0) return NM_OK;  // an empty buffer may be a NULL pointer
     if (!in) return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: in is NULL");
     if (!out_q && !out_f32 && !dbg_seg) return fail(NM_ERR_INVALID_ARG, "nm_pwl_apply: no output");
     const bool vec = aligned(in, 16) && (!out_f32 || aligned(out_f32, 16)) &&
                      (!out_q || aligned(out_q, 4)) && (!dbg_seg || aligned(dbg_seg, 8));
-    const size_t shmem = sizeof(float2) * (size_t)t.nseg;
+    const bool two = t.cellmap != nullptr;  // two-level form: merged segments + one byte per cell
+    const size_t shmem = two ? 8 * (size_t)t.nkb + (((size_t)t.nseg + 7) & ~(size_t)7) : sizeof(float2) * (size_t)t.nseg;
     const int blocks = blocks_for(vec ? (n + 3) / 4 : n, kRowThreads);
-    if (vec)
-        hipLaunchKernelGGL(pwl_apply_kernel<true>, dim3(blocks), dim3(kRowThreads), shmem,
-                           (hipStream_t)stream, in, in_dtype == NM_DT_I32, alpha, (long)n, t,
-                           out_inv_scale, out_q, out_f32, dbg_seg);
-    else
-        hipLaunchKernelGGL(pwl_apply_kernel<false>, dim3(blocks), dim3(kRowThreads), shmem,
-                           (hipStream_t)stream, in, in_dtype == NM_DT_I32, alpha, (long)n, t,
-                           out_inv_scale, out_q, out_f32, dbg_seg);
+    auto launch = [&](auto kern) {
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(kRowThreads), shmem, (hipStream_t)stream, in,
+                           in_dtype == NM_DT_I32, alpha, (long)n, t, out_inv_scale, out_q, out_f32, dbg_seg);
+    };
+    if (vec && two) launch(pwl_apply_kernel<true, true>);
+    else if (vec) launch(pwl_apply_kernel<true, false>);
+    else if (two) launch(pwl_apply_kernel<false, true>);
+    else launch(pwl_apply_kernel<false, false>);
     return check_hip(hipGetLastError(), "nm_pwl_apply launch");
 }
 

@@ -38,7 +38,7 @@ int32_t check_hip(hipError_t e, const char* what)
     return fail(NM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-int32_t get_dev_table(const nm_tables* t, int32_t idx, DevTable* dt, const char* what)
+int32_t get_dev_table(const nm_tables* t, int32_t idx, DevTable* dt, const char* what, bool two_level)
 {
     if (!t) return fail(NM_ERR_INVALID_ARG, "%s: tables is NULL", what);
     if (idx < 0 || idx >= (int32_t)t->tables.size())
@@ -51,6 +51,12 @@ int32_t get_dev_table(const nm_tables* t, int32_t idx, DevTable* dt, const char*
     dt->inv_w = h.inv_w;
     dt->nseg = h.desc.nseg;
     dt->clamp_input = (h.desc.flags & NM_TABLE_CLAMP_INPUT) ? 1 : 0;
+    dt->ckb = nullptr; dt->cellmap = nullptr; dt->nkb = 0;
+    if (two_level && !h.cellmap.empty()) {
+        dt->ckb = t->d_blob + h.cblob_offset;
+        dt->cellmap = reinterpret_cast<const uint8_t*>(t->d_blob + h.map_offset);
+        dt->nkb = (int)h.ck.size();
+    }
     return NM_OK;
 }
 
@@ -188,16 +194,46 @@ static int32_t build_host(const nm_table_desc* d, float* k, float* b, float* inv
     return NM_OK;
 }
 
+// The two-level form of a table whose neighbouring cells share parameters (Algorithm 2 merges
+// them): runs of bit-identical {k, b} become one segment each.  At most 256 segments (the map holds
+// one byte per cell).
+static int32_t make_compact(HostTable& h)
+{
+    h.ck.clear(); h.cb.clear(); h.cellmap.assign(h.k.size(), 0);
+    for (size_t i = 0; i < h.k.size(); ++i) {
+        const bool same = i > 0 && std::memcmp(&h.k[i], &h.k[i - 1], sizeof(float)) == 0 &&
+                          std::memcmp(&h.b[i], &h.b[i - 1], sizeof(float)) == 0;
+        if (!same) {
+            if (h.ck.size() == 256)
+                return fail(NM_ERR_UNSUPPORTED, "NM_TABLE_COMPACT: more than 256 merged segments");
+            h.ck.push_back(h.k[i]);
+            h.cb.push_back(h.b[i]);
+        }
+        h.cellmap[i] = (uint8_t)(h.ck.size() - 1);
+    }
+    return NM_OK;
+}
+
 static int32_t upload(nm_tables* t, hipStream_t stream)
 {
     size_t total = 0;
     for (auto& h : t->tables) {
         h.blob_offset = total;
         total += ((size_t)h.desc.nseg + 15) / 16 * 16;  // 128-byte aligned tables
+        if (!h.cellmap.empty()) {
+            h.cblob_offset = total;
+            total += (h.ck.size() + 15) / 16 * 16;
+            h.map_offset = total;
+            total += (h.cellmap.size() + 127) / 128 * 16;  // bytes, rounded up to 128, in float2 units
+        }
     }
     std::vector<float2> blob(total, make_float2(0.f, 0.f));
-    for (auto& h : t->tables)
+    for (auto& h : t->tables) {
         for (int i = 0; i < h.desc.nseg; ++i) blob[h.blob_offset + i] = make_float2(h.k[i], h.b[i]);
+        for (size_t i = 0; i < h.ck.size(); ++i) blob[h.cblob_offset + i] = make_float2(h.ck[i], h.cb[i]);
+        if (!h.cellmap.empty())
+            std::memcpy(reinterpret_cast<uint8_t*>(blob.data() + h.map_offset), h.cellmap.data(), h.cellmap.size());
+    }
     int32_t rc = check_hip(hipGetDevice(&t->device), "hipGetDevice");
     if (rc) return rc;
     rc = check_hip(hipMalloc((void**)&t->d_blob, total * sizeof(float2)), "hipMalloc(tables)");
@@ -259,6 +295,10 @@ static int32_t make_tables(const nm_table_desc* descs, int32_t n, const float* c
         } else {
             build_host(&descs[i], h.k.data(), h.b.data(), &h.inv_w, &h.n_distinct);
         }
+        if (descs[i].flags & NM_TABLE_COMPACT) {
+            int32_t rc = make_compact(h);
+            if (rc) { delete t; return rc; }
+        }
     }
     int32_t rc = upload(t, (hipStream_t)stream);
     if (rc) {
@@ -294,6 +334,21 @@ int32_t nm_tables_get(const nm_tables* t, int32_t idx, nm_table_desc* desc, floa
     if (k_host) std::memcpy(k_host, h.k.data(), sizeof(float) * h.k.size());
     if (b_host) std::memcpy(b_host, h.b.data(), sizeof(float) * h.b.size());
     if (inv_w) *inv_w = h.inv_w;
+    return NM_OK;
+}
+
+int32_t nm_tables_get_compact(const nm_tables* t, int32_t idx, int32_t* n_segments, uint8_t* cell_to_segment,
+                              float* k_host, float* b_host)
+{
+    if (!t) return fail(NM_ERR_INVALID_ARG, "nm_tables_get_compact: tables is NULL");
+    if (idx < 0 || idx >= (int32_t)t->tables.size())
+        return fail(NM_ERR_INVALID_ARG, "nm_tables_get_compact: index %d out of range", idx);
+    const HostTable& h = t->tables[idx];
+    if (h.cellmap.empty()) return fail(NM_ERR_INVALID_ARG, "nm_tables_get_compact: table %d was not built with NM_TABLE_COMPACT", idx);
+    if (n_segments) *n_segments = (int32_t)h.ck.size();
+    if (cell_to_segment) std::memcpy(cell_to_segment, h.cellmap.data(), h.cellmap.size());
+    if (k_host) std::memcpy(k_host, h.ck.data(), sizeof(float) * h.ck.size());
+    if (b_host) std::memcpy(b_host, h.cb.data(), sizeof(float) * h.cb.size());
     return NM_OK;
 }
 

@@ -39,6 +39,17 @@ int main(void)
                 if (nm < 1 || nm > nseg) { printf("FAILED merged count\n"); return 1; }
                 free(k); free(b);
             }
+    {   /* a merged table in its own form, evaluated directly */
+        const int np_ = 37;
+        int32_t* st = NEW(int32_t, np_); float* k = NEW(float, np_); float* b = NEW(float, np_); float iw; int32_t nm = 0;
+        CHECK(nmo_table_build_merged_direct(0, -8, 8, np_, 0.03, 2, 0.0, st, k, b, &iw, &nm));
+        nmo_merged_table mt = {-8, 8, iw, np_, 1, nm, st, k, b};
+        const int n = 301;
+        float* x = NEW(float, n); fill_f32(x, n, -12, 12); x[0] = NAN; x[1] = INFINITY; x[2] = -INFINITY;
+        float* y = NEW(float, n); int8_t* q = NEW(int8_t, n); uint16_t* s1 = NEW(uint16_t, n); uint16_t* s2 = NEW(uint16_t, n);
+        CHECK(nmo_pwl_apply_merged(x, NMO_DT_F32, 1.0f, n, &mt, 9.0f, q, y, s1, s2));
+        free(st); free(k); free(b); free(x); free(y); free(q); free(s1); free(s2);
+    }
     double* xs = NEW(double, 17);
     if (nmo_size_optimize_builtin(0, -4.0, 4.0, 0.5, 0.1, xs, 16) < 1) { printf("FAILED size_optimize\n"); return 1; }
     free(xs);

@@ -213,6 +213,97 @@ def test_elastic_tables_encoder_layer(oracle, label, flags, e_th, dk_th):
     assert np.allclose(got["y_f32"], want["y_f32"], rtol=1e-4, atol=1e-5)
 
 
+# ---- merged tables looked up in two levels (cell of x, merged segment of the cell) ------------
+
+@pytest.mark.parametrize("name,lo,hi,nprim,dk", [("gelu", -4.0, 4.0, 16, 0.1), ("gelu", -8.0, 8.0, 256, 0.01),
+                                                  ("exp", -16.0, 0.0, 128, 0.01), ("rsqrt", 1e-3, 64.0, 256, 0.05)])
+@pytest.mark.parametrize("clamp", [0, 1])
+def test_two_level_tables_pwl_apply(oracle, name, lo, hi, nprim, dk, clamp):
+    """nm_pwl_apply on a merged table kept in two levels (NM_TABLE_COMPACT) against the oracle's
+    direct evaluation of the merged table (search over Algorithm 2's start points): outputs exact,
+    reported cell exact, the library's cell map equal to the oracle's start points.  First case: the
+    paper's worked GELU example (threshold 0.1, primary length 0.5: 8 segments for 16 cells)."""
+    mt = oracle.build_table_merged_direct(OID[name], lo, hi, nprim, dk, flags=clamp)
+    te, _ = oracle.build_table_merged(OID[name], lo, hi, nprim, dk, flags=clamp)
+    flags = nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT | clamp
+    injected = nm.nm_tables_from_arrays([(name, lo, hi, nprim, flags)], [te.k], [te.b])
+    built = nm.nm_build_tables([(name, lo, hi, nprim, flags, 0.0, dk)])
+    for tb, exact in ((injected, True), (built, False)):
+        cmap, ck, cb = nm.nm_tables_get_compact(tb, 0)
+        assert np.array_equal(cmap, mt.cell_to_segment()) and ck.size == mt.nseg
+        if exact:
+            assert np.array_equal(ck, mt.k) and np.array_equal(cb, mt.b)
+        print(f"[two-level] {name} {nprim} cells -> {ck.size} segments: {8 * ck.size + nprim} bytes in LDS "
+              f"instead of {8 * nprim}")
+    x = np.concatenate([W.sweep_values(lo, hi, 60001, seed=3), np.array([np.nan, np.inf, -np.inf], np.float32)])
+    y, q, s, c = oracle.pwl_apply_merged(x, mt, out_inv_scale=21.0)
+    for n in (x.size, 7):   # vector path and the scalar tail path
+        yq = torch.empty(n, dtype=torch.int8, device=DEV)
+        yf = torch.empty(n, dtype=torch.float32, device=DEV)
+        ys = torch.empty(n, dtype=torch.int16, device=DEV)
+        nm.nm_pwl_apply(dev(x[:n]), 1.0, injected, 0, 21.0, out_q=yq, out_f32=yf, dbg_seg=ys)
+        assert_exact(host(ys).view(np.uint16), c[:n], "two-level: primary cell")
+        assert_exact(mt.cell_to_segment()[host(ys).view(np.uint16)], s[:n], "two-level: merged segment")
+        assert_exact(host(yq), q[:n], "two-level: int8")
+        assert_f32_close(host(yf), y[:n], "two-level: fp32")
+    yq = torch.empty(x.size, dtype=torch.int8, device=DEV)
+    nm.nm_pwl_apply(dev(x), 1.0, built, 0, 21.0, out_q=yq)
+    d = np.abs(host(yq).astype(int) - q.astype(int))
+    assert d.max() <= 1 and (d > 0).mean() < 1e-3
+    # int32 input
+    a = np.random.default_rng(8).integers(-40000, 40000, size=30001, dtype=np.int32)
+    alpha = float(np.float32((hi - lo) / 60000.0))
+    y, q, s, c = oracle.pwl_apply_merged(a, mt, alpha=alpha, out_inv_scale=9.0)
+    yq = torch.empty(a.size, dtype=torch.int8, device=DEV)
+    nm.nm_pwl_apply(dev(a), alpha, injected, 0, 9.0, out_q=yq)
+    assert_exact(host(yq), q, "two-level: int32 input")
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 384, 256), (70, 50, 96)])
+def test_two_level_table_gemm_epilogue(oracle, M, N, K):
+    """nm_gemm_pwl with a two-level GELU table (streaming and generic kernels): the same outputs as
+    the oracle's GEMM followed by its direct evaluation of the merged table."""
+    lo, hi, nprim, dk = -8.0, 8.0, 128, 0.01
+    mt = oracle.build_table_merged_direct(OID["gelu"], lo, hi, nprim, dk)
+    te, _ = oracle.build_table_merged(OID["gelu"], lo, hi, nprim, dk)
+    dt = nm.nm_tables_from_arrays([("gelu", lo, hi, nprim, nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT)], [te.k], [te.b])
+    d = W.gemm_inputs(M, N, K, seed=M + K + 2, full_range=False)
+    alpha = float(np.float32(6.0 / (20 * 20 * np.sqrt(K))))
+    pre = oracle.gemm_pwl(d["A"], d["W"], bias=d["bias"], alpha=alpha)["y"]      # fp32 pre-activations
+    y, q, s, c = oracle.pwl_apply_merged(pre.ravel(), mt, out_inv_scale=25.0)
+    oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+    of = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    seg = torch.empty((M, N), dtype=torch.int16, device=DEV)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=dt, table_idx=0,
+                   out_inv_scale=25.0, out_q=oq, out_f32=of, dbg_seg=seg)
+    assert_exact(host(seg).view(np.uint16).ravel(), c, "two-level gemm: primary cell")
+    assert_exact(host(oq).ravel(), q, "two-level gemm: int8")
+    assert_f32_close(host(of).ravel(), y, "two-level gemm: fp32")
+    oq2 = torch.empty_like(oq)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=dt, table_idx=0,
+                   out_inv_scale=25.0, out_q=oq2)
+    assert_exact(host(oq2).ravel(), q, "two-level gemm: int8 only")
+    assert len(np.unique(s)) > 5
+
+
+def test_two_level_table_limits():
+    """More than 256 merged segments do not fit the byte map; the other entry points use a two-level
+    table's expanded form (same results)."""
+    with pytest.raises(nm.NmError) as ei:
+        nm.nm_build_tables([("exp", -16.0, 0.0, 512, nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT, 0.0, 0.0)])
+    assert ei.value.status == nm.NM_ERR_UNSUPPORTED
+    t = nm.nm_build_tables([("rsqrt", 1e-3, 64.0, 64, nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT, 0.0, 0.05),
+                            ("rsqrt", 1e-3, 64.0, 64, nm.NM_TABLE_MERGE, 0.0, 0.05)])
+    x = torch.randn((33, 200), device=DEV)
+    g = torch.ones(200, device=DEV)
+    b = torch.zeros(200, device=DEV)
+    q0 = torch.empty((33, 200), dtype=torch.int8, device=DEV)
+    q1 = torch.empty_like(q0)
+    nm.nm_layernorm_pwl(x, g, b, 1e-5, t, 0, 20.0, out_q=q0)
+    nm.nm_layernorm_pwl(x, g, b, 1e-5, t, 1, 20.0, out_q=q1)
+    assert torch.equal(q0, q1)
+
+
 # ---- softmax-PWL ------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("rows,cols", [(37, 1), (37, 5), (19, 64), (101, 128), (37, 200), (37, 512),

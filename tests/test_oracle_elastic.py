@@ -140,3 +140,77 @@ def test_merged_table_is_chords_over_merged_segments(oracle):
         k, b = float(t.k[cells[0]]), float(t.b[cells[0]])
         for x in (a, c):  # the line passes through f at both ends of the merged segment
             assert abs(k * x + b - TRUTH["gelu"](x)) < 2e-6
+
+
+# ---- a merged table evaluated in its own form (start points + one line per merged segment) ----
+
+def test_merged_direct_paper_example(oracle):
+    """The paper's worked GELU example (threshold 0.1, primary length 0.5): the start points are
+    multiples of the primary length, -1.5 is not among them, -2 and -1 are."""
+    g = read_gold("alg2_gelu_example.txt")
+    dlx, dk = float(g["dlx"][0]), float(g["dk_th"][0])
+    t = oracle.build_table_merged_direct(FID["gelu"], -4.0, 4.0, int(round(8.0 / dlx)), dk)
+    starts = -4.0 + t.start_cell * dlx
+    assert float(g["merged_interior_point"][0]) not in starts
+    assert -2.0 in starts and -1.0 in starts and t.start_cell[0] == 0
+    assert np.all(np.diff(t.start_cell) > 0)
+    xs = oracle.size_optimize(FID["gelu"], -4.0, 4.0, dlx, dk)
+    assert np.array_equal(starts, xs)
+
+
+@pytest.mark.parametrize("name,nprim,dk", [("gelu", 16, 0.1), ("gelu", 256, 0.01), ("exp", 64, 0.02),
+                                            ("recip", 128, 0.005), ("rsqrt", 256, 0.01), ("sqrt", 37, 0.03)])
+@pytest.mark.parametrize("clamp", [0, 1])
+def test_merged_direct_equals_expanded(oracle, name, nprim, dk, clamp):
+    """Evaluating the merged table directly (search over its start points) gives bit for bit what
+    the expanded table gives with the uniform look-up, for every input incl. break points, values
+    outside the range, infinities and NaN; with and without Algorithm 3's shift."""
+    lo, hi = RANGES[name]
+    for bias in (0, oracle.FLAG_BIAS_CORRECT):
+        t = oracle.build_table_merged_direct(FID[name], lo, hi, nprim, dk, flags=bias | clamp)
+        te, n = oracle.build_table_merged(FID[name], lo, hi, nprim, dk, flags=bias | clamp)
+        assert n == t.nseg and 1 <= n <= nprim
+        w = (hi - lo) / nprim
+        brk = (lo + w * np.arange(nprim + 1)).astype(np.float32)
+        x = np.concatenate([np.linspace(lo - 2.0, hi + 2.0, 40001).astype(np.float32), brk,
+                            np.nextafter(brk, np.float32(-np.inf)), np.nextafter(brk, np.float32(np.inf)),
+                            np.array([np.nan, np.inf, -np.inf], np.float32)])
+        y, q, s, c = oracle.pwl_apply_merged(x, t, out_inv_scale=13.0)
+        y2, q2, s2 = oracle.pwl_apply(x, te, out_inv_scale=13.0)
+        assert np.array_equal(y.view(np.uint32), y2.view(np.uint32))
+        assert np.array_equal(q, q2) and np.array_equal(c, s2)
+        assert np.array_equal(t.cell_to_segment()[c], s)
+        # the expanded table holds each merged segment's line in every cell of the segment
+        assert np.array_equal(te.k, t.k[t.cell_to_segment()]) and np.array_equal(te.b, t.b[t.cell_to_segment()])
+
+
+def test_merged_direct_segment_search_against_if_chain(oracle):
+    """The segment found by the search equals a plain if-chain over the start points in binary64
+    (inputs a safe distance from the break points, where fp32 rounding cannot matter)."""
+    lo, hi, nprim = -4.0, 4.0, 32
+    t = oracle.build_table_merged_direct(FID["gelu"], lo, hi, nprim, 0.05)
+    w = (hi - lo) / nprim
+    starts = lo + t.start_cell.astype(np.float64) * w
+    rng = np.random.default_rng(5)
+    x = rng.uniform(lo - 1, hi + 1, 20000).astype(np.float32)
+    x = x[np.min(np.abs(x[:, None].astype(np.float64) - (lo + w * np.arange(nprim + 1))[None, :]), axis=1) > 1e-4]
+    _, _, s, _ = oracle.pwl_apply_merged(x, t)
+    want = np.zeros(x.size, np.int64)
+    for i, xi in enumerate(x.astype(np.float64)):
+        seg = 0
+        for j, st in enumerate(starts):
+            if xi >= st:
+                seg = j
+        want[i] = seg
+    assert np.array_equal(s.astype(np.int64), want)
+
+
+def test_merged_direct_limits(oracle):
+    """Threshold 0 keeps every cell whose slope differs (all of them for a strictly convex function);
+    an infinite threshold leaves one segment."""
+    t0 = oracle.build_table_merged_direct(FID["exp"], -8.0, 0.0, 64, 0.0)
+    assert t0.nseg == 64 and np.array_equal(t0.start_cell, np.arange(64))
+    t1 = oracle.build_table_merged_direct(FID["exp"], -8.0, 0.0, 64, 1e30)
+    assert t1.nseg == 1 and t1.start_cell[0] == 0
+    chord = oracle.build_table(FID["exp"], -8.0, 0.0, 1)
+    assert t1.k[0] == chord.k[0] and t1.b[0] == chord.b[0]
