@@ -88,6 +88,9 @@ def main():
                          "primary segments whose slopes differ by less are merged)")
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layernorm", choices=("auto", "fold", "separate"), default="auto",
+                    help="LayerNorm inside the out-projection / FFN2 kernels (fold), as kernels of its own "
+                         "(separate), or the library's choice (auto)")
     ap.add_argument("--graph", action="store_true", help="replay a HIP graph holding one step instead of launching it from the host")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 64 MiB device copy (reference for rocprofv3 --pmc "
@@ -124,7 +127,8 @@ def main():
     tables = nm.nm_build_tables(specs)          # the library's own table builder
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)  # noqa: E731
     devws = [{n: t(q[n]) for n in nm.LAYER_PTRS} for q in stack]
-    descs = [nm.make_layer_desc(q, dw, tables) for q, dw in zip(stack, devws)]
+    ln_flags = {"auto": 0, "fold": nm.NM_LAYER_FOLD_LAYERNORM, "separate": nm.NM_LAYER_NO_FOLD_LAYERNORM}[args.layernorm]
+    descs = [nm.make_layer_desc(q, dw, tables, flags=ln_flags) for q, dw in zip(stack, devws)]
     devw, desc = devws[0], descs[0]
     ws = torch.empty(nm.nm_encoder_stack_workspace(descs), dtype=torch.uint8, device=dev)
     x = t(p["x"])
@@ -393,7 +397,7 @@ def main():
                data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
                                              nseg=cfg["nseg"], layers=n_layers,
                                              table_flags=args.table_flags, dk_th=args.dk_th,
-                                             distinct_segments=distinct, launch=launch),
+                                             distinct_segments=distinct, launch=launch, layernorm=args.layernorm),
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
                summary=summary,
                parity=parity)

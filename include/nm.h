@@ -313,7 +313,14 @@ typedef struct {
     float inv_s_out;
     const nm_tables* tables;
     int32_t gelu_idx, exp_idx, recip_idx, rsqrt_idx;
+    int32_t flags;                /* NM_LAYER_* (0: the library chooses) */
 } nm_layer_desc;
+
+/* Steps 5+6 and 8+9 as one kernel each (the LayerNorm runs in the epilogue of the matrix product,
+ * on workgroups that own whole rows; the fp32 tensor between them never reaches memory).  Needs
+ * H = 768 or 1024 and aligned operands; where that does not hold, or taps of the fp32 tensors are
+ * asked for, the two-kernel path runs.  Results are identical either way. */
+enum { NM_LAYER_FOLD_LAYERNORM = 1, NM_LAYER_NO_FOLD_LAYERNORM = 2 };
 
 /* Optional device buffers that receive the intermediate tensors (any may be NULL; a non-NULL
  * buffer is used as that tensor's storage, so it costs nothing extra). */

@@ -27,6 +27,7 @@ EXPORTS = ("nm_last_error", "nm_version", "nm_table_build_host", "nm_build_table
            "nm_encoder_stack_workspace", "nm_encoder_stack", "nm_conv2d_workspace", "nm_conv2d_pwl",
            "nm_maxpool_i8", "nm_avgpool_i8", "nm_cnn_workspace", "nm_cnn_run")
 NM_OP_CONV, NM_OP_MAXPOOL, NM_OP_AVGPOOL, NM_OP_GEMM = 0, 1, 2, 3
+NM_LAYER_FOLD_LAYERNORM, NM_LAYER_NO_FOLD_LAYERNORM = 1, 2
 NM_NOALLOC_MAX_WORKSPACE = 64 << 20  # bytes of the buffer built into the library (nm_encoder_layer_noalloc)
 
 
@@ -80,7 +81,7 @@ class LayerDesc(C.Structure):
                 [("eps1", C.c_float), ("eps2", C.c_float)] +
                 [(n, C.c_float) for n in LAYER_FLOATS] +
                 [("tables", C.c_void_p)] +
-                [(n, C.c_int32) for n in ("gelu_idx", "exp_idx", "recip_idx", "rsqrt_idx")])
+                [(n, C.c_int32) for n in ("gelu_idx", "exp_idx", "recip_idx", "rsqrt_idx", "flags")])
 
 
 class LayerTaps(C.Structure):
@@ -349,7 +350,7 @@ def nm_attention_pwl(qkv, B, S, H, heads, alpha_scores, tables: Tables, exp_idx,
                                    _ptr(scores_out), _ptr(p_out), _stream(stream)))
 
 
-def make_layer_desc(params: dict, dev: dict, tables: Tables, idx=(0, 1, 2, 3)) -> LayerDesc:
+def make_layer_desc(params: dict, dev: dict, tables: Tables, idx=(0, 1, 2, 3), flags=0) -> LayerDesc:
     """params: numbers (dims, eps, fp32 multipliers); dev: device tensors of the weights."""
     d = LayerDesc()
     for n in ("B", "S", "H", "heads", "F"):
@@ -361,6 +362,7 @@ def make_layer_desc(params: dict, dev: dict, tables: Tables, idx=(0, 1, 2, 3)) -
         setattr(d, n, float(params[n]))
     d.tables = tables.handle
     d.gelu_idx, d.exp_idx, d.recip_idx, d.rsqrt_idx = idx
+    d.flags = flags
     return d
 
 

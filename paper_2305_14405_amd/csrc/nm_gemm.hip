@@ -787,9 +787,36 @@ static int32_t launch_stream_conv(GemmParams& p, int epi, size_t table_bytes, hi
     }
 }
 
+// The LayerNorm-folding kernel: workgroups of 64 rows x all N columns (eight wavefronts, each all 64
+// rows of N / 8 columns), 64-byte k-slices so that two ring stages of 64 + N rows fit LDS.
+bool gemm_folds_layernorm(const GemmArgs& g)
+{
+    if (force_generic() || g.conv || g.w_is_kn || g.outer_count * g.inner_count != 1) return false;
+    if (g.N != 768 && g.N != 1024) return false;
+    if (g.K % 64 != 0 || g.K / 64 < 3 || g.alpha_vec || g.has_table || !g.resid || !g.ln_gamma || !g.ln_beta) return false;
+    if (!(g.ln_out_q || g.ln_out_f32)) return false;
+    const bool al = aligned(g.A, 16) && g.lda % 16 == 0 && aligned(g.W, 16) && g.ldw % 16 == 0 && aligned(g.resid, 16) &&
+                    g.ldo == g.N && aligned(g.ln_gamma, 16) && aligned(g.ln_beta, 16) &&
+                    (!g.ln_out_q || aligned(g.ln_out_q, 16)) && (!g.ln_out_f32 || aligned(g.ln_out_f32, 16)) &&
+                    (!g.bias || aligned(g.bias, 4));
+    return al && (int64_t)g.M * g.lda < (1LL << 32) && (int64_t)g.N * g.ldw < (1LL << 32);
+}
+
 int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
 {
     if (g.M == 0) return NM_OK;
+    if (g.ln) {
+        if (!gemm_folds_layernorm(g)) return fail(NM_ERR_UNSUPPORTED, "gemm: this shape does not fold the LayerNorm");
+        GemmParams q{};
+        q.M = g.M; q.N = g.N; q.K = g.K; q.A = g.A; q.lda = g.lda; q.W = g.W; q.ldw = g.ldw; q.inner_count = 1;
+        q.bias = g.bias; q.alpha = g.alpha; q.resid = g.resid; q.resid_scale = g.resid_scale; q.ldo = g.ldo;
+        q.ln_gamma = g.ln_gamma; q.ln_beta = g.ln_beta; q.ln_eps = g.ln_eps; q.ln_inv_scale = g.ln_inv_scale;
+        q.ln_table = g.ln_table; q.ln_out_q = g.ln_out_q; q.ln_out_f32 = g.ln_out_f32;
+        int32_t rc = g.N == 768 ? launch_tile_epi<64, 768, 1, 8, 2, EPI_F32_RESID_LN, 64>(q, 0, stream)
+                                : launch_tile_epi<64, 1024, 1, 8, 2, EPI_F32_RESID_LN, 64>(q, 0, stream);
+        if (rc) return rc;
+        return check_hip(hipGetLastError(), "gemm + LayerNorm launch");
+    }
     GemmParams p{};
     p.M = g.M; p.N = g.N; p.K = g.K;
     p.A = g.A; p.lda = g.lda; p.W = g.W; p.ldw = g.ldw;
@@ -806,6 +833,8 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     p.cH = g.cH; p.cW = g.cW; p.cCin = g.cCin; p.cKw = g.cKw; p.cStride = g.cStride; p.cPad = g.cPad;
     p.cHo = g.cHo; p.cWo = g.cWo;
     p.out_q = g.out_q; p.out_f32 = g.out_f32; p.out_acc = g.out_acc; p.dbg_seg = g.dbg_seg;
+    p.ln_gamma = g.ln_gamma; p.ln_beta = g.ln_beta; p.ln_eps = g.ln_eps; p.ln_inv_scale = g.ln_inv_scale;
+    p.ln_table = g.ln_table; p.ln_out_q = g.ln_out_q; p.ln_out_f32 = g.ln_out_f32;
 
     // 16-byte loads need every row start and every batch offset on a 16-byte boundary
     const bool a_al = aligned(g.A, 16) && g.lda % 16 == 0 && g.a_outer % 16 == 0 && g.a_inner % 16 == 0;

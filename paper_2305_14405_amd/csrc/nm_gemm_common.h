@@ -38,6 +38,14 @@ struct GemmParams {
     int32_t* out_acc;
     uint16_t* dbg_seg;
     int tiles_m, tiles_n;
+    // LayerNorm-PWL folded into the epilogue (EPI_F32_RESID_LN): y = fma(d * r, gamma, beta) with
+    // r = PWL_rsqrt(var + eps); outputs its int8 code and / or fp32 value, row stride N
+    const float* ln_gamma;
+    const float* ln_beta;
+    float ln_eps, ln_inv_scale;
+    DevTable ln_table;
+    int8_t* ln_out_q;
+    float* ln_out_f32;
     // convolution in matrix form (streaming kernel with kConv): row m of A is the output position
     // (b, ho, wo), column k the (tap, channel) pair; A points to the NHWC image tensor
     int cH, cW, cCin, cKw, cStride, cPad, cHo, cWo;
@@ -50,7 +58,9 @@ __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >>
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * kBK + ((chunk ^ swz(row)) << 4); }
 
 
-enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4, EPI_Q_TABLE_RESID = 5 };
+enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4, EPI_Q_TABLE_RESID = 5, EPI_F32_RESID_LN = 6 };
+// EPI_F32_RESID_LN: EPI_F32_RESID followed by LayerNorm-PWL over the row, inside the kernel: the tile
+// covers whole rows (tile kernel only).
 // EPI_Q_TABLE_RESID: int8 residual, table (no input clamp), int8 output: the last convolution of a
 // residual block (sum with the shortcut, ReLU).
 

@@ -28,20 +28,22 @@ namespace nm {
 // issues almost twice as fast that way as with four wavefronts of 128 x 96 (measured: a single
 // wavefront cannot issue dependent-free vector instructions back to back at the SIMD's full rate).
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int kEpi>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int kEpi, int BK = 128>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(GemmParams p)
 {
-    constexpr int BK = 128;
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int ROWS = BM + BN;
     constexpr int CPR = BK / 16;
     constexpr int RPI = 64 / CPR;
-    constexpr int NBLK = ROWS / RPI;
-    constexpr int LB = NBLK / NW;            // 1 KB blocks per wavefront and k-slice
-    constexpr int LBA = (BM / RPI) / NW;     // ... of which A rows
-    constexpr int STAGE_BYTES = ROWS * BK;
+    constexpr int NBLK = ROWS / RPI;         // 1 KB blocks of a k-slice
+    constexpr int LB = (NBLK + NW - 1) / NW; // ... per wavefront: when they do not split evenly the last
+                                             // ones are fetched twice into spare LDS behind the stage
+    constexpr int ABLK = BM / RPI;           // blocks that hold A rows
+    constexpr bool kEven = NBLK % NW == 0 && ABLK % NW == 0;
+    constexpr int LBA = ABLK / NW;           // A blocks per wavefront (even split)
+    constexpr int STAGE_BYTES = LB * NW * 1024;
     constexpr int KS = BK / 32;
     constexpr int NR = TM + TN;              // fragments per k-step
     constexpr int NMF = TM * TN;             // matrix instructions per k-step
@@ -50,9 +52,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
     constexpr int RPS = (NR + POST - 1) / POST;         // fragment reads per slot there
     constexpr int RPS2 = (NR + NMF - 1) / NMF;          // ... and in the other k-steps
     constexpr int DPS = (LB + POST + NMF - 1) / (POST + NMF);  // refill loads per slot (those slots and the next k-step's)
-    static_assert(NBLK % NW == 0 && (BM / RPI) % NW == 0, "blocks split evenly");
+    static_assert(ROWS % RPI == 0 && BM % RPI == 0, "whole blocks");
     static_assert(TM >= 2 && TN >= 2 && KS % 2 == 0, "wavefront tile");
-    static_assert(kEpi == EPI_Q || kEpi == EPI_Q_TABLE || kEpi == EPI_F32_RESID, "epilogues of the tile kernel");
+    static_assert(kEpi == EPI_Q || kEpi == EPI_Q_TABLE || kEpi == EPI_F32_RESID || kEpi == EPI_F32_RESID_LN,
+                  "epilogues of the tile kernel");
+    static_assert(kEpi != EPI_F32_RESID_LN || WAVES_M == 1, "row statistics: a wavefront holds all rows of its columns");
+    constexpr bool kResid = kEpi == EPI_F32_RESID || kEpi == EPI_F32_RESID_LN;
 
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     float* s_bias = reinterpret_cast<float*>(smem + STAGES * STAGE_BYTES);
@@ -85,7 +90,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
         const int blk = wave + b * NW;
         const int r = blk * RPI + lane / CPR;
         const int chunk = (lane % CPR) ^ swz_bk<BK>(r);
-        if (b < LBA) voff[b] = (unsigned)min(m0 + r, p.M - 1) * (unsigned)p.lda + 16u * chunk;
+        const bool is_a = kEven ? b < LBA : blk < ABLK;  // wave-uniform
+        if (is_a) voff[b] = (unsigned)min(m0 + r, p.M - 1) * (unsigned)p.lda + 16u * chunk;
         else voff[b] = (unsigned)min(n0 + r - BM, p.N - 1) * (unsigned)p.ldw + 16u * chunk;
     }
     const unsigned lds_base = (unsigned)(uintptr_t)smem;
@@ -93,7 +99,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
     const int8_t* __restrict__ gW = p.W;
     auto issue1 = [&](int kt, int slot, int b) {
         const unsigned dst = lds_base + slot * STAGE_BYTES + (wave + b * NW) * 1024;
-        dma16s((b < LBA ? gA : gW) + (long)kt * BK, voff[b], dst);
+        const bool is_a = kEven ? b < LBA : wave + b * NW < ABLK;
+        dma16s((is_a ? gA : gW) + (long)kt * BK, voff[b], dst);
     };
     const int nk = p.K / BK;  // >= STAGES + 1 (host)
 #pragma unroll
@@ -123,7 +130,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
     constexpr int CPRW = BN / 16;
     constexpr int RPT = (BM * CPRW + 64 * NW - 1) / (64 * NW);
     v4i res_reg[RPT];
-    if (kEpi == EPI_F32_RESID) {
+    if (kResid) {
 #pragma unroll
         for (int t = 0; t < RPT; ++t) {
             const int c = tid + t * 64 * NW, row = c / CPRW, cc = c % CPRW;
@@ -243,7 +250,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
     }
     constexpr int RW = BN + 16;  // row stride of the residual image
     int8_t* s_res = smem;        // in the ring, which is free now
-    if (kEpi == EPI_F32_RESID) {
+    if (kResid) {
 #pragma unroll
         for (int t = 0; t < RPT; ++t) {
             const int c = tid + t * 64 * NW, row = c / CPRW, cc = c % CPRW;
@@ -261,7 +268,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
 #pragma unroll
         for (int g = 0; g < 4; ++g) bi[j][g] = *reinterpret_cast<const v4f*>(s_bias + wave_n + 32 * j + 8 * g + 4 * frag_half);
     constexpr int NG = TM * TN * 4;  // groups of four columns per lane
-    if (kEpi == EPI_Q_TABLE || kEpi == EPI_Q) {
+    if constexpr (kEpi == EPI_Q_TABLE || kEpi == EPI_Q) {
         constexpr int SW = WN + 16;
         static_assert(NW * WM * SW <= STAGES * STAGE_BYTES, "patch fits the ring");
         int8_t* patch = smem + wave * (WM * SW);
@@ -332,7 +339,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
             const int mr = m0 + wave_m + row, n = n0 + wave_n + 16 * cc;
             if (full || (mr < p.M && n < p.N)) *reinterpret_cast<v4i*>(p.out_q + (long)mr * p.ldo + n) = rows[t];
         }
-    } else {
+    } else if constexpr (kEpi == EPI_F32_RESID) {
         const float rs = p.resid_scale;
 #pragma unroll
         for (int G = 0; G < NG; ++G) {
@@ -348,14 +355,122 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
             const int m = m0 + row, n = n0 + cl;
             if (full || (m < p.M && n < p.N)) *reinterpret_cast<v4f*>(p.out_f32 + (long)m * p.ldo + n) = y;
         }
+    } else {
+        // ---- fp32 result + residual, then LayerNorm-PWL over the row (the tile covers whole rows:
+        // BN == N, n0 == 0, and every wavefront holds all BM rows of its WN columns).  Row sums keep
+        // the normative order: column group G (four consecutive columns) belongs to accumulator
+        // G % 64, an accumulator adds its groups in increasing G and each group's elements in
+        // increasing column, starting from +0; the 64 accumulators of a row are then combined by the
+        // butterfly 32, 16, 8, 4, 2, 1.  Groups 64 apart live in different wavefronts, so the
+        // accumulators pass through LDS: round s adds the groups G with G / 64 == s.
+        static_assert(BM <= 64 && BN % 256 == 0 && WN % 4 == 0, "row block shape");
+        constexpr int NS = (BN / 4 + 63) / 64;         // rounds
+        float* s_part = reinterpret_cast<float*>(smem + BM * RW);  // [BM][64] accumulators, behind the residual image
+        float* s_stat = s_part + BM * 64;                           // [BM] mean, then [BM] scale
+        static_assert(BM * RW + (BM * 64 + 2 * BM) * 4 <= STAGES * STAGE_BYTES, "statistics fit the ring");
+        const float rs = p.resid_scale;
+        const float inv_L = (float)(1.0 / (double)BN);
+        // the fp32 values of the lane (they replace the accumulators)
+        float xv[TM][TN][16];
+#pragma unroll
+        for (int G = 0; G < NG; ++G) {
+            const int i = G % TM, jg = G / TM, j = jg / 4, g = jg % 4;
+            const int row = 32 * i + frag_row, cl = wave_n + 32 * j + 8 * g + 4 * frag_half;
+            const unsigned rw = *reinterpret_cast<const unsigned*>(s_res + row * RW + cl);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = __builtin_fmaf((float)acc[i][j][4 * g + e], alpha, bi[j][g][e]);
+                xv[i][j][4 * g + e] = __builtin_fmaf((float)(int)(int8_t)(rw >> (8 * e)), rs, v);
+            }
+        }
+        // one pass over the row: SQ == false sums x, SQ == true sums fma(d, d, .)
+        auto row_pass = [&](auto sq_c) {
+            constexpr bool SQ = decltype(sq_c)::value;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int G = (wave_n + 32 * j + 8 * g + 4 * frag_half) >> 2;  // column group in the row
+                        if ((G >> 6) != s) continue;                                 // wave-uniform (G and G ^ 1 share a round)
+#pragma unroll
+                        for (int i = 0; i < TM; ++i) {
+                            float* slot = s_part + (32 * i + frag_row) * 64 + (G & 63);
+                            float a = s == 0 ? 0.0f : *slot;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                a = SQ ? __builtin_fmaf(xv[i][j][4 * g + e], xv[i][j][4 * g + e], a) : a + xv[i][j][4 * g + e];
+                            *slot = a;
+                        }
+                    }
+                __syncthreads();
+            }
+            // butterfly over the 64 accumulators of each row: lane = accumulator
+            for (int row = wave; row < BM; row += NW) {
+                float v = s_part[row * 64 + lane];
+#pragma unroll
+                for (int mask = 32; mask >= 1; mask >>= 1) v = v + __shfl_xor(v, mask, 64);
+                if (lane == 0) s_stat[row] = v * inv_L;
+            }
+            __syncthreads();
+        };
+        row_pass(std::false_type{});
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const float mu = s_stat[32 * i + frag_row];
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) xv[i][j][v] = xv[i][j][v] - mu;
+        }
+        __syncthreads();  // every lane has read its means before the variances overwrite them
+        row_pass(std::true_type{});
+        // scale of a row: r = PWL_rsqrt(var + eps), one look-up per row
+        if (tid < BM) {
+            int sr;
+            const float u = s_stat[tid] + p.ln_eps;
+            s_stat[BM + tid] = pwl_eval(u, p.ln_table, p.ln_table.kb, sr);
+        }
+        __syncthreads();
+        // y = fma(d * r, gamma, beta); int8 rows leave through an LDS image as 16-byte stores
+        int8_t* s_out = smem;  // [BM][RW], over the residual image (its last reader was the first loop above)
+        const float inv = p.ln_inv_scale;
+#pragma unroll
+        for (int G = 0; G < NG; ++G) {
+            const int i = G % TM, jg = G / TM, j = jg / 4, g = jg % 4;
+            const int row = 32 * i + frag_row, cl = wave_n + 32 * j + 8 * g + 4 * frag_half;
+            const float r = s_stat[BM + row];
+            const v4f ga = *reinterpret_cast<const v4f*>(p.ln_gamma + cl);
+            const v4f be = *reinterpret_cast<const v4f*>(p.ln_beta + cl);
+            v4f y;
+            int q[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                y[e] = __builtin_fmaf(xv[i][j][4 * g + e] * r, ga[e], be[e]);
+                q[e] = requant(y[e], inv);
+            }
+            if (p.ln_out_q) *reinterpret_cast<unsigned*>(s_out + row * RW + cl) = pack4(q[0], q[1], q[2], q[3]);
+            if (p.ln_out_f32 && m0 + row < p.M) *reinterpret_cast<v4f*>(p.ln_out_f32 + (long)(m0 + row) * BN + cl) = y;
+        }
+        if (p.ln_out_q) {
+            __syncthreads();
+            for (int c = tid; c < BM * CPRW; c += 64 * NW) {
+                const int row = c / CPRW, cc = c % CPRW;
+                if (m0 + row < p.M)
+                    *reinterpret_cast<v4i*>(p.ln_out_q + (long)(m0 + row) * BN + 16 * cc) =
+                        *reinterpret_cast<const v4i*>(s_out + row * RW + 16 * cc);
+            }
+        }
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int kEpi>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int kEpi, int BK = 128>
 static int32_t launch_tile_epi(GemmParams& p, size_t table_bytes, hipStream_t s)
 {
-    auto kern = gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, kEpi>;
-    const size_t shmem = (size_t)STAGES * (BM + BN) * 128 + BN * sizeof(float) + table_bytes;
+    auto kern = gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, kEpi, BK>;
+    constexpr int NW = WAVES_M * WAVES_N, NBLK = (BM + BN) * BK / 1024;
+    const size_t shmem = (size_t)STAGES * ((NBLK + NW - 1) / NW * NW) * 1024 + BN * sizeof(float) + table_bytes;
     static std::once_flag once;  // one attribute call per instantiation
     static int32_t once_rc = NM_OK;
     std::call_once(once, [&] {

@@ -89,6 +89,15 @@ struct GemmArgs {
     float* out_f32 = nullptr;
     int32_t* out_acc = nullptr;
     uint16_t* dbg_seg = nullptr;
+    // LayerNorm-PWL of the fp32 result, folded into the kernel when the shape allows it (else the
+    // caller runs the row kernel): gamma / beta [N], rsqrt table, int8 and / or fp32 output [M, N]
+    int ln = 0;
+    const float* ln_gamma = nullptr;
+    const float* ln_beta = nullptr;
+    float ln_eps = 0.0f, ln_inv_scale = 1.0f;
+    DevTable ln_table{};
+    int8_t* ln_out_q = nullptr;
+    float* ln_out_f32 = nullptr;
     // conv != 0: A is an NHWC image [B, cH, cW, cCin] and row m = (b, ho, wo) of the matrix is
     // gathered from it (K = kh * cKw * cCin, tap major); M = B * cHo * cWo
     int conv = 0;
@@ -96,6 +105,8 @@ struct GemmArgs {
 };
 
 int32_t launch_gemm(const GemmArgs& g, hipStream_t stream);
+// True when launch_gemm would fold the LayerNorm described by g.ln_* into the GEMM kernel.
+bool gemm_folds_layernorm(const GemmArgs& g);
 
 int32_t launch_softmax(const void* in, int32_t in_dtype, float alpha, int64_t rows, int32_t cols,
                        const DevTable& t_exp, const DevTable& t_recip, float out_inv_scale,

@@ -189,7 +189,10 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
             return rc;
         if ((rc = nm_attn_context(pm, qkv, B, S, H, nh, d->alpha_ctx, d->inv_s_ctx, ctx, stream))) return rc;
     }
-    // 5: output projection + bias + residual(x) -> fp32
+    // 5: output projection + bias + residual(x) -> fp32;  6: LayerNorm-PWL -> int8.  One kernel when
+    // the caller asks for it and the shape allows (the fp32 tensor then never reaches memory, so not
+    // when its tap is wanted), else two.
+    const bool want_fold = (d->flags & NM_LAYER_FOLD_LAYERNORM) && !(d->flags & NM_LAYER_NO_FOLD_LAYERNORM);
     {
         GemmArgs g;
         g.M = M; g.N = H; g.K = H;
@@ -197,12 +200,18 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
         g.bias = d->bo; g.alpha = d->alpha_o;
         g.resid = x; g.resid_scale = d->resid1_scale;
         g.ldo = H; g.out_f32 = attn;
-        if ((rc = launch_gemm(g, stream))) return rc;
+        g.ln_gamma = d->gamma1; g.ln_beta = d->beta1; g.ln_eps = d->eps1; g.ln_inv_scale = d->inv_s_ln1;
+        g.ln_table = t_rsqrt; g.ln_out_q = ln1;
+        if (want_fold && !(taps && taps->attn) && gemm_folds_layernorm(g)) {
+            g.ln = 1;
+            if ((rc = launch_gemm(g, stream))) return rc;
+        } else {
+            if ((rc = launch_gemm(g, stream))) return rc;
+            if ((rc = launch_layernorm(attn, d->gamma1, d->beta1, d->eps1, M, H, t_rsqrt, d->inv_s_ln1, ln1,
+                                       nullptr, nullptr, stream)))
+                return rc;
+        }
     }
-    // 6: LayerNorm-PWL -> int8
-    if ((rc = launch_layernorm(attn, d->gamma1, d->beta1, d->eps1, M, H, t_rsqrt, d->inv_s_ln1, ln1,
-                               nullptr, nullptr, stream)))
-        return rc;
     // 7: FFN1 + bias, GELU-PWL in the epilogue -> int8
     {
         GemmArgs g;
@@ -214,7 +223,7 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
         g.ldo = F; g.out_q = ffn1;
         if ((rc = launch_gemm(g, stream))) return rc;
     }
-    // 8: FFN2 + bias + residual(LN1 output) -> fp32
+    // 8: FFN2 + bias + residual(LN1 output) -> fp32;  9: LayerNorm-PWL -> layer output (one kernel or two, as above)
     {
         GemmArgs g;
         g.M = M; g.N = H; g.K = F;
@@ -222,9 +231,14 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
         g.bias = d->b2; g.alpha = d->alpha_2;
         g.resid = ln1; g.resid_scale = d->resid2_scale;
         g.ldo = H; g.out_f32 = ffn2;
+        g.ln_gamma = d->gamma2; g.ln_beta = d->beta2; g.ln_eps = d->eps2; g.ln_inv_scale = d->inv_s_out;
+        g.ln_table = t_rsqrt; g.ln_out_q = y_q; g.ln_out_f32 = y_f32;
+        if (want_fold && !(taps && taps->ffn2) && gemm_folds_layernorm(g)) {
+            g.ln = 1;
+            return launch_gemm(g, stream);
+        }
         if ((rc = launch_gemm(g, stream))) return rc;
     }
-    // 9: LayerNorm-PWL -> layer output
     return launch_layernorm(ffn2, d->gamma2, d->beta2, d->eps2, M, H, t_rsqrt, d->inv_s_out, y_q, y_f32,
                             nullptr, stream);
 }

@@ -771,6 +771,53 @@ def test_encoder_stack_full_depth(oracle, name, n_layers, batch):
     assert len(np.unique(want["y_q"])) > 100  # the stack's output is not degenerate
 
 
+def run_layer_folded(oracle, cfg, p, flags):
+    """The layer without taps of the fp32 tensors (so that the LayerNorms may run inside the matrix
+    products' kernels); returns the oracle's and the library's ln1 / y_q / y_f32."""
+    specs = [W.table_ranges(cfg)[n] for n in ("gelu", "exp", "recip", "rsqrt")]
+    ot, dt = both_tables(oracle, specs)
+    want = oracle.encoder_layer(p, dict(zip(("gelu", "exp", "recip", "rsqrt"), ot)), p["x"])
+    M, H = cfg["B"] * cfg["S"], cfg["H"]
+    devw = {n: dev(p[n]) for n in nm.LAYER_PTRS}
+    desc = nm.make_layer_desc(p, devw, dt, flags=flags)
+    ws = torch.empty(nm.nm_encoder_layer_workspace(desc), dtype=torch.uint8, device=DEV)
+    taps = dict(ln1=torch.empty((M, H), dtype=torch.int8, device=DEV))
+    yq = torch.full((M, H), 99, dtype=torch.int8, device=DEV)
+    yf = torch.full((M, H), float("nan"), dtype=torch.float32, device=DEV)
+    nm.nm_encoder_layer(desc, dev(p["x"]), yq, yf, ws, taps=taps)
+    got = dict(ln1=host(taps["ln1"]), y_q=host(yq), y_f32=host(yf))
+    yq2 = torch.full((M, H), 99, dtype=torch.int8, device=DEV)
+    nm.nm_encoder_layer(desc, dev(p["x"]), yq2, None, ws)      # int8 output only
+    assert_exact(host(yq2), got["y_q"], "folded LayerNorm, int8 output only")
+    return want, got
+
+
+@pytest.mark.parametrize("name", ["bert_base_s512", "bert_large_s512"])
+def test_encoder_layer_layernorm_folded_into_gemm(oracle, name):
+    """NM_LAYER_FOLD_LAYERNORM: out-projection + LayerNorm and FFN2 + LayerNorm as one kernel each
+    (H = 768 and H = 1024, full-size layers): same int8 and fp32 results as the oracle."""
+    cfg = W.config(name)
+    want, got = run_layer_folded(oracle, cfg, W.layer_params(name, 0), nm.NM_LAYER_FOLD_LAYERNORM)
+    assert_exact(got["ln1"], want["ln1"], f"{name} folded: ln1")
+    assert_exact(got["y_q"], want["y_q"], f"{name} folded: y_q")
+    assert_f32_close(got["y_f32"], want["y_f32"], f"{name} folded: y_f32")
+
+
+@pytest.mark.parametrize("B,S,H,heads,F", [(3, 50, 768, 12, 1024), (1, 70, 1024, 16, 512)])
+def test_encoder_layer_layernorm_folded_ragged_rows(oracle, B, S, H, heads, F):
+    """The folded kernels on row counts that are not a multiple of their 64-row blocks."""
+    cfg = dict(B=B, S=S, H=H, heads=heads, F=F, nseg=64)
+    base = "bert_base_layer" if H == 768 else "bert_large_s512"
+    p = W.with_scales(W.layer_tensors(cfg, 3), W.stored_scales(base, 0))
+    want, got = run_layer_folded(oracle, cfg, p, nm.NM_LAYER_FOLD_LAYERNORM)
+    assert_exact(got["ln1"], want["ln1"], "folded, ragged rows: ln1")
+    assert_exact(got["y_q"], want["y_q"], "folded, ragged rows: y_q")
+    assert_f32_close(got["y_f32"], want["y_f32"], "folded, ragged rows: y_f32")
+    # the flag that forbids folding gives the same results through the two-kernel path
+    want2, got2 = run_layer_folded(oracle, cfg, p, nm.NM_LAYER_NO_FOLD_LAYERNORM)
+    assert_exact(got2["y_q"], got["y_q"], "two-kernel path")
+
+
 def test_encoder_layer_with_library_built_tables(oracle):
     """The product path builds its own tables (host code of the library).  They may differ from
     the oracle's in the last bit, so int8 outputs are compared to within one code."""
