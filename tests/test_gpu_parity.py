@@ -77,6 +77,11 @@ def test_pwl_apply_fp32_and_int32(oracle, ti):
         assert_exact(host(ys).view(np.uint16), s, f"pwl_apply seg {f}")
         assert_exact(host(yq), q, f"pwl_apply int8 {f}")
         assert_f32_close(host(yf), y, f"pwl_apply fp32 {f}")
+        # fp32 in, int8 out alone (the kernel variant the layer's activations take), guard bytes behind
+        yq1 = torch.full((x.size + 16,), 55, dtype=torch.int8, device=DEV)
+        nm.nm_pwl_apply(xd, 1.0, dt, ti, inv, out_q=yq1, n=x.size)
+        assert_exact(host(yq1)[:x.size], q, f"pwl_apply int8 alone {f}")
+        assert np.all(host(yq1)[x.size:] == 55)
     # int32 input with a dequantisation scale
     g = np.random.default_rng(ti)
     a = g.integers(-40000, 40000, size=70001, dtype=np.int32)
