@@ -43,13 +43,17 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "encoder_layer_bert_base_layer_pmc
 KERNEL_SOURCES = os.path.join(ROOT, "paper_2305_14405_amd", "csrc")
 
 
+# the sources the encoder layer's kernels are built from (the convolution path is not among them)
+LAYER_KERNEL_SOURCES = ("nm_device.h", "nm_internal.h", "nm_gemm_common.h", "nm_gemm_tile.h", "nm_gemm.hip",
+                        "nm_rows.hip", "nm_attention.hip", "nm_layer.cpp")
+
+
 def kernel_source_hash():
     import hashlib
     h = hashlib.sha256()
-    for name in sorted(os.listdir(KERNEL_SOURCES)):
-        if name.endswith((".hip", ".h", ".cpp")):
-            with open(os.path.join(KERNEL_SOURCES, name), "rb") as f:
-                h.update(name.encode() + b"\0" + f.read())
+    for name in LAYER_KERNEL_SOURCES:
+        with open(os.path.join(KERNEL_SOURCES, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()[:16]
 
 

@@ -38,6 +38,7 @@ struct GemmParams {
     int32_t* out_acc;
     uint16_t* dbg_seg;
     int tiles_m, tiles_n;
+    int group_m;  // tile kernel: tile rows per group of the XCD-aware tile order
     // LayerNorm-PWL folded into the epilogue (EPI_F32_RESID_LN): y = fma(d * r, gamma, beta) with
     // r = PWL_rsqrt(var + eps); outputs its int8 code and / or fp32 value, row stride N
     const float* ln_gamma;

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
     int id = blockIdx.x;
     const int ntiles = p.tiles_m * p.tiles_n;
     if (ntiles % 8 == 0) id = (id % 8) * (ntiles / 8) + id / 8;
-    constexpr int GM = 8;
+    const int GM = p.group_m;
     const int group = id / (GM * p.tiles_n);
     const int first_m = group * GM;
     const int gm = min(GM, p.tiles_m - first_m);
@@ -465,6 +465,27 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
     }
 }
 
+// Tile rows per group of the tile order.  Workgroup i runs on XCD i % 8, and the kernel hands XCD x the
+// x-th eighth of the tile sequence, which walks groups of group_m tile rows column by column.  An
+// eighth of r x c tiles reads r * BM rows of A and c * BN rows of W through that XCD's L2: pick the
+// r (a divisor of the eighth, with whole columns: tiles_n % c == 0) that makes this sum smallest.
+static inline int xcd_group_rows(int tiles_m, int tiles_n, int BM, int BN)
+{
+    const int ntiles = tiles_m * tiles_n;
+    if (ntiles % 8 != 0) return 8;
+    const int share = ntiles / 8;
+    int best = 8;
+    long best_cost = -1;
+    for (int r = 1; r <= tiles_m && r <= share; ++r) {
+        if (share % r != 0 || tiles_m % r != 0) continue;
+        const int c = share / r;
+        if (c > tiles_n || tiles_n % c != 0) continue;
+        const long cost = (long)r * BM + (long)c * BN;
+        if (best_cost < 0 || cost < best_cost) best_cost = cost, best = r;
+    }
+    return best;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int kEpi, int BK = 128>
 static int32_t launch_tile_epi(GemmParams& p, size_t table_bytes, hipStream_t s)
 {
@@ -481,6 +502,7 @@ static int32_t launch_tile_epi(GemmParams& p, size_t table_bytes, hipStream_t s)
     if (once_rc) return once_rc;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
+    p.group_m = xcd_group_rows(p.tiles_m, p.tiles_n, BM, BN);
     hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n), dim3(64 * WAVES_M * WAVES_N), shmem, s, p);
     return NM_OK;
 }
