@@ -99,14 +99,34 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 64 MiB device copy (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE runs of this script)")
+    ap.add_argument("--also", default="bert_base_s512,resnet50",
+                    help="with the default workload and the CPU leg on: further workloads measured briefly "
+                         "(few steps, one oracle run each) and reported under other_workloads; 'none' to skip")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    out = run_workload(args)
+    if args.workload == "bert_base_layer" and not args.no_cpu_baseline and args.also != "none":
+        others = []
+        for name in args.also.split(","):
+            a = argparse.Namespace(**vars(args))
+            a.workload, a.steps, a.warmup, a.kernel_reps, a.brief = name, 10, 2, 10, True
+            o = run_workload(a)
+            others.append({k: o[k] for k in ("value", "unit", "ms_per_step", "steps", "config", "roofline",
+                                             "cpu_baseline", "parity")})
+        out["other_workloads"] = others
+    print(json.dumps(out))
+
+
+def run_workload(args):
     if args.workload.startswith("resnet"):
         return bench_resnet(args)
+    return bench_encoder(args)
 
+
+def bench_encoder(args):
     import numpy as np
     import torch
 
@@ -287,8 +307,117 @@ def main():
         kernels.append(dict(kernel=name, bound=bound, ms=round(ms, 5), achieved=round(ach, 2),
                             peak=peak, unit=unit, frac=round(ach / peak, 4),
                             traffic=traffic.get(name)))
+    brief = getattr(args, "brief", False)
     # the HBM-bound row kernels again at shapes beyond the last-level cache (the softmax shape is
     # that of the 12-layer BERT-base workload: 16 x 12 x 512 rows of 512 scores)
+    big, rot = [], []
+    if not brief:
+        big, rot = row_kernel_sections(torch, nm, timed, tables, devw, p, dev, M, H, F, B, nh, S)
+    # the slowest kernel the layer really launches (at shapes the fused attention kernel covers, the
+    # stand-alone softmax row kernel is timed for its bandwidth figure only)
+    fused_attn = H // nh == 64 and S <= 512 and H % 16 == 0
+    for k in kernels:
+        k["in_layer"] = k["kernel"] not in (("softmax_pwl" if fused_attn else "attention_fused"),
+                                            "ffn1_gelu_gemm_stress")
+    dom = max((k for k in kernels if k["in_layer"]), key=lambda k: k["ms"])
+    roofline = dict(bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"], unit=dom["unit"],
+                    frac=dom["frac"], traffic=dom["traffic"], kernel=dom["kernel"],
+                    note="int8 MFMA rate (2 operations per multiply-accumulate)" if dom["bound"] == "mfma"
+                    else "plain vector ALU, 18 scalar operations per attention score")
+    gemm_ops = sum(2.0 * M * n * k for n, k in ((3 * H, H), (H, H), (F, H), (H, F)))
+    gemm_ms = sum(k["ms"] for k in kernels if k["bound"] == "mfma" and k["in_layer"])
+    row_bytes = float(B * nh * S * S * 5 + 2 * M * H * 5)
+    ln_ms = next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl")
+    row_ms = next(k["ms"] for k in kernels if k["kernel"] == "softmax_pwl") + 2 * ln_ms
+    summary = dict(int8_mfma_util_pct=round(100 * gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
+                   nonlinear_hbm_gbs=round(row_bytes / (row_ms * 1e-3) / 1e9, 1),
+                   nonlinear_hbm_gbs_large=round(sum(k["achieved"] for k in big) / len(big), 1) if big else None,
+                   sum_kernel_ms=round(sum(k["ms"] for k in kernels if k["in_layer"]) + ln_ms, 4),
+                   note="softmax_pwl is the stand-alone row kernel (timed on its own; the layer uses the "
+                        "fused attention kernel at this shape); layernorm_pwl runs twice per layer")
+
+    # ---- CPU oracle on the host cores: the same workload, bounded sample ----------------------
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        oid = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
+        if args.table_flags & 4:
+            ot = {n: O.build_table_merged(oid[s[0]], s[1], s[2], s[3], args.dk_th, flags=args.table_flags & ~4)[0]
+                  for n, s in zip(order, specs)}
+        else:
+            ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3], flags=args.table_flags) for n, s in zip(order, specs)}
+        # bounded sample: whole batch for the 128-token layer, two sequences of layer 0 otherwise
+        # (sequences are independent, so a batch subset is the same computation on fewer rows)
+        b_sub = B if (n_layers == 1 and M * H <= 4096 * 768) else min(B, 2)
+        p_sub = dict(p, B=b_sub)
+        x_sub = np.ascontiguousarray(p["x"][:b_sub * S])
+        n_runs, c0 = 0, time.perf_counter()
+        while True:
+            want = O.encoder_layer(p_sub, ot, x_sub, want_taps=False)
+            n_runs += 1
+            if brief or time.perf_counter() - c0 > 12.0 or n_runs >= 64:
+                break
+        cpu_s = (time.perf_counter() - c0) / n_runs
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        sample = (f"{n_runs} run(s) of layer 0 of {args.workload} on {b_sub} of {B} sequences, "
+                  f"{cpu_s:.2f} s per run")
+        if n_layers > 1:
+            sample += f"; value = {b_sub} / ({n_layers} layers x {cpu_s:.2f} s), extrapolated linearly over layers"
+        cpu_baseline = dict(value=round(b_sub / (cpu_s * n_layers), 4), unit="sequences/s", cores=cores,
+                            kind="oracle", sample=sample)
+        # the same on one thread (one sequence, one run), for the per-core figure
+        try:
+            if brief:
+                raise OSError("skipped in a brief run")
+            import ctypes
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            p_one = dict(p, B=1)
+            c1 = time.perf_counter()
+            O.encoder_layer(p_one, ot, np.ascontiguousarray(p["x"][:S]), want_taps=False)
+            one_s = time.perf_counter() - c1
+            gomp.omp_set_num_threads(cores)
+            cpu_baseline["value_1_thread"] = round(1.0 / (one_s * n_layers), 4)
+        except OSError:
+            pass
+        # layer 0 on the GPU (library-built tables) against the oracle's layer 0 (oracle-built tables:
+        # may differ in the last bit), and against the oracle's true-function mode (same quantised
+        # network, exact GELU / exp / 1/x / rsqrt in binary64): the PWL approximation error
+        yq0 = torch.empty((M, H), dtype=torch.int8, device=dev)
+        yf0 = torch.empty((M, H), dtype=torch.float32, device=dev)
+        nm.nm_encoder_layer(desc, x, yq0, yf0, ws)
+        torch.cuda.synchronize()
+        rows = b_sub * S
+        diff = np.abs(yq0[:rows].cpu().numpy().astype(int) - want["y_q"].astype(int))
+        exact, _ = O.encoder_layer_exact(p_sub, ot, x_sub, quantise=True)
+        err = np.abs(yf0[:rows].cpu().numpy().astype(np.float64) - exact)
+        parity = dict(int8_max_abs_diff=int(diff.max()), int8_mismatch_frac=float((diff > 0).mean()),
+                      note="layer 0, library-built tables vs oracle-built tables (may differ in the last bit)",
+                      pwl_vs_exact_f=dict(nseg=int(cfg["nseg"]), max_abs=float(err.max()),
+                                          mean_abs=float(err.mean()),
+                                          rel_rms=float(np.sqrt((err ** 2).mean() / (exact ** 2).mean())),
+                                          note="fp32 layer-0 output vs the oracle's true-function mode "
+                                               "of the same quantised layer"))
+
+    out = dict(metric="PWL encoder-layer sequences/s + int8 MFMA util % + nonlinear-kernel HBM GB/s",
+               value=round(seq_per_s, 1), unit="sequences/s", n_gpus=1, steps=args.steps,
+               warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True,
+               scaling="weak", vs_baseline=None, dtype="int8", dtype_note="int8 operands, int32 accumulation, fp32 epilogue",
+               data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
+                                             nseg=cfg["nseg"], layers=n_layers,
+                                             table_flags=args.table_flags, dk_th=args.dk_th,
+                                             distinct_segments=distinct, launch=launch, layernorm=args.layernorm),
+               roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
+               row_kernels_layer_shape_rotated=rot,
+               summary=summary,
+               parity=parity)
+    return out
+
+
+def row_kernel_sections(torch, nm, timed, tables, devw, p, dev, M, H, F, B, nh, S):
+    """the HBM-bound row kernels at shapes beyond the last-level cache, and at the layer's own shapes
+    over rotated buffer sets"""
     big = []
     xl = torch.randn((65536, H), device=dev)
     ol = torch.empty((65536, H), dtype=torch.int8, device=dev)
@@ -339,104 +468,7 @@ def main():
                     achieved=round(M * F * 5 / (ms * 1e-3) / 1e9, 1)))
     for k in big + rot:
         k.update(bound="hbm", peak=PEAK_HBM_GBS, unit="GB/s", frac=round(k["achieved"] / PEAK_HBM_GBS, 4))
-    # the slowest kernel the layer really launches (at shapes the fused attention kernel covers, the
-    # stand-alone softmax row kernel is timed for its bandwidth figure only)
-    fused_attn = H // nh == 64 and S <= 512 and H % 16 == 0
-    for k in kernels:
-        k["in_layer"] = k["kernel"] not in (("softmax_pwl" if fused_attn else "attention_fused"),
-                                            "ffn1_gelu_gemm_stress")
-    dom = max((k for k in kernels if k["in_layer"]), key=lambda k: k["ms"])
-    roofline = dict(bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"], unit=dom["unit"],
-                    frac=dom["frac"], traffic=dom["traffic"], kernel=dom["kernel"],
-                    note="int8 MFMA rate (2 operations per multiply-accumulate)" if dom["bound"] == "mfma"
-                    else "plain vector ALU, 18 scalar operations per attention score")
-    gemm_ops = sum(2.0 * M * n * k for n, k in ((3 * H, H), (H, H), (F, H), (H, F)))
-    gemm_ms = sum(k["ms"] for k in kernels if k["bound"] == "mfma" and k["in_layer"])
-    row_bytes = float(B * nh * S * S * 5 + 2 * M * H * 5)
-    ln_ms = next(k["ms"] for k in kernels if k["kernel"] == "layernorm_pwl")
-    row_ms = next(k["ms"] for k in kernels if k["kernel"] == "softmax_pwl") + 2 * ln_ms
-    summary = dict(int8_mfma_util_pct=round(100 * gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
-                   nonlinear_hbm_gbs=round(row_bytes / (row_ms * 1e-3) / 1e9, 1),
-                   nonlinear_hbm_gbs_large=round(sum(k["achieved"] for k in big) / len(big), 1),
-                   sum_kernel_ms=round(sum(k["ms"] for k in kernels if k["in_layer"]) + ln_ms, 4),
-                   note="softmax_pwl is the stand-alone row kernel (timed on its own; the layer uses the "
-                        "fused attention kernel at this shape); layernorm_pwl runs twice per layer")
-
-    # ---- CPU oracle on the host cores: the same workload, bounded sample ----------------------
-    cpu_baseline = None
-    parity = None
-    if not args.no_cpu_baseline:
-        from oracle import oracle as O
-        oid = {"gelu": O.F_GELU, "exp": O.F_EXP, "recip": O.F_RECIP, "rsqrt": O.F_RSQRT}
-        if args.table_flags & 4:
-            ot = {n: O.build_table_merged(oid[s[0]], s[1], s[2], s[3], args.dk_th, flags=args.table_flags & ~4)[0]
-                  for n, s in zip(order, specs)}
-        else:
-            ot = {n: O.build_table(oid[s[0]], s[1], s[2], s[3], flags=args.table_flags) for n, s in zip(order, specs)}
-        # bounded sample: whole batch for the 128-token layer, two sequences of layer 0 otherwise
-        # (sequences are independent, so a batch subset is the same computation on fewer rows)
-        b_sub = B if (n_layers == 1 and M * H <= 4096 * 768) else min(B, 2)
-        p_sub = dict(p, B=b_sub)
-        x_sub = np.ascontiguousarray(p["x"][:b_sub * S])
-        n_runs, c0 = 0, time.perf_counter()
-        while True:
-            want = O.encoder_layer(p_sub, ot, x_sub, want_taps=False)
-            n_runs += 1
-            if time.perf_counter() - c0 > 12.0 or n_runs >= 64:
-                break
-        cpu_s = (time.perf_counter() - c0) / n_runs
-        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        sample = (f"{n_runs} run(s) of layer 0 of {args.workload} on {b_sub} of {B} sequences, "
-                  f"{cpu_s:.2f} s per run")
-        if n_layers > 1:
-            sample += f"; value = {b_sub} / ({n_layers} layers x {cpu_s:.2f} s), extrapolated linearly over layers"
-        cpu_baseline = dict(value=round(b_sub / (cpu_s * n_layers), 4), unit="sequences/s", cores=cores,
-                            kind="oracle", sample=sample)
-        # the same on one thread (one sequence, one run), for the per-core figure
-        try:
-            import ctypes
-            gomp = ctypes.CDLL("libgomp.so.1")
-            gomp.omp_set_num_threads(1)
-            p_one = dict(p, B=1)
-            c1 = time.perf_counter()
-            O.encoder_layer(p_one, ot, np.ascontiguousarray(p["x"][:S]), want_taps=False)
-            one_s = time.perf_counter() - c1
-            gomp.omp_set_num_threads(cores)
-            cpu_baseline["value_1_thread"] = round(1.0 / (one_s * n_layers), 4)
-        except OSError:
-            pass
-        # layer 0 on the GPU (library-built tables) against the oracle's layer 0 (oracle-built tables:
-        # may differ in the last bit), and against the oracle's true-function mode (same quantised
-        # network, exact GELU / exp / 1/x / rsqrt in binary64): the PWL approximation error
-        yq0 = torch.empty((M, H), dtype=torch.int8, device=dev)
-        yf0 = torch.empty((M, H), dtype=torch.float32, device=dev)
-        nm.nm_encoder_layer(desc, x, yq0, yf0, ws)
-        torch.cuda.synchronize()
-        rows = b_sub * S
-        diff = np.abs(yq0[:rows].cpu().numpy().astype(int) - want["y_q"].astype(int))
-        exact, _ = O.encoder_layer_exact(p_sub, ot, x_sub, quantise=True)
-        err = np.abs(yf0[:rows].cpu().numpy().astype(np.float64) - exact)
-        parity = dict(int8_max_abs_diff=int(diff.max()), int8_mismatch_frac=float((diff > 0).mean()),
-                      note="layer 0, library-built tables vs oracle-built tables (may differ in the last bit)",
-                      pwl_vs_exact_f=dict(nseg=int(cfg["nseg"]), max_abs=float(err.max()),
-                                          mean_abs=float(err.mean()),
-                                          rel_rms=float(np.sqrt((err ** 2).mean() / (exact ** 2).mean())),
-                                          note="fp32 layer-0 output vs the oracle's true-function mode "
-                                               "of the same quantised layer"))
-
-    out = dict(metric="PWL encoder-layer sequences/s + int8 MFMA util % + nonlinear-kernel HBM GB/s",
-               value=round(seq_per_s, 1), unit="sequences/s", n_gpus=1, steps=args.steps,
-               warmup=args.warmup, ms_per_step=round(ms_per_step, 5), higher_is_better=True,
-               scaling="weak", vs_baseline=None, dtype="int8", dtype_note="int8 operands, int32 accumulation, fp32 epilogue",
-               data="synthetic", config=dict(workload=args.workload, B=B, S=S, H=H, heads=nh, F=F,
-                                             nseg=cfg["nseg"], layers=n_layers,
-                                             table_flags=args.table_flags, dk_th=args.dk_th,
-                                             distinct_segments=distinct, launch=launch, layernorm=args.layernorm),
-               roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, row_kernels_large=big,
-               row_kernels_layer_shape_rotated=rot,
-               summary=summary,
-               parity=parity)
-    print(json.dumps(out))
+    return big, rot
 
 
 def graph_timed(torch, fn, reps):
@@ -590,7 +622,7 @@ def bench_resnet(args):
             op = next(o for o, d in convs if o["name"] == c[1])
             ops = 2.0 * B * op["Ho"] ** 2 * op["Cout"] * op["k"] ** 2 * op["Cin"]
             ach = ops / (ms * 1e-3) / 1e12
-            entry.update(bound="mfma", achieved=round(ach, 1), peak=PEAK_INT8_TOPS, unit="TFLOP/s",
+            entry.update(bound="mfma", achieved=round(ach, 1), peak=PEAK_INT8_TOPS, unit="TOP/s",
                          frac=round(ach / PEAK_INT8_TOPS, 4),
                          shape=f"M={B * op['Ho'] ** 2} N={op['Cout']} K={op['k'] ** 2 * op['Cin']} "
                                f"k{op['k']} s{op['stride']}")
@@ -599,7 +631,7 @@ def bench_resnet(args):
     dom = max(conv_k, key=lambda k: k["ms"])
     total_ops = sum(2.0 * B * o["Ho"] ** 2 * o["Cout"] * o["k"] ** 2 * o["Cin"] for o, _ in convs)
     conv_ms = sum(k["ms"] for k in conv_k)
-    roofline = dict(bound="mfma", achieved=dom["achieved"], peak=PEAK_INT8_TOPS, unit="TFLOP/s", frac=dom["frac"],
+    roofline = dict(bound="mfma", achieved=dom["achieved"], peak=PEAK_INT8_TOPS, unit="TOP/s", frac=dom["frac"],
                     traffic=None, kernel=dom["kernel"] + " (" + dom["shape"] + ")",
                     note="int8 MFMA rate in TOP/s (2 ops per multiply-accumulate); slowest convolution")
     summary = dict(int8_mfma_util_pct=round(100 * total_ops / (conv_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
@@ -632,7 +664,7 @@ def bench_resnet(args):
                            widths=list(cfg["widths"]), classes=cfg["classes"], launch=launch_mode,
                            ms_per_step_eager=round(ms_eager, 5)),
                roofline=roofline, cpu_baseline=cpu_baseline, kernels=kernels, summary=summary, parity=parity)
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":
