@@ -187,27 +187,22 @@ def test_resnet50_full_size_layers_batch4(oracle):
     assert np.array_equal(host(got["logits"]).view(np.uint32), want["logits"].view(np.uint32)), "logits"
 
 
-def test_resnet50_batch64_launch_configuration_sampled(oracle):
-    """The configuration bench.py times (batch 64: other tile choices than small batches take).
-    Images are independent, so the oracle runs the first two and every tensor of the GPU run is
-    compared on those two images; the remaining images are checked for the property that holds at
-    any size: an image that is a copy of image 0 gives the same logits as image 0."""
+def test_resnet50_batch64_launch_configuration(oracle):
+    """The configuration bench.py times (batch 64: other tile choices than small batches take):
+    every tensor of the network and the logits, all 64 images, against the oracle (~10 s of oracle
+    time).  Two images are copies of others, which must give identical results as well."""
     p = W.resnet_params("resnet50", 0, batch=64)
     p["x"] = p["x"].copy()
     p["x"][63] = p["x"][0]
     p["x"][37] = p["x"][1]
     ot, dt = relu_tables(oracle)
-    p2 = dict(p)
-    p2["x"] = p["x"][:2]
-    p2["B"] = 2
-    want = oracle.resnet_forward(p2, keep=True)
+    want = oracle.resnet_forward(p, keep=True)
     got = run_resnet_gpu(p, dt)
     for k, v in want["tensors"].items():
-        assert np.array_equal(host(got["tensors"][k])[:2], v), f"resnet50 batch 64: tensor {k}"
+        assert np.array_equal(host(got["tensors"][k]), v), f"resnet50 batch 64: tensor {k}"
     logits = host(got["logits"])
-    assert np.array_equal(logits[:2].view(np.uint32), want["logits"].view(np.uint32))
+    assert np.array_equal(logits.view(np.uint32), want["logits"].view(np.uint32))
     assert np.array_equal(logits[63], logits[0]) and np.array_equal(logits[37], logits[1])
-    assert np.array_equal(host(got["tensors"]["s3b2c"])[63], host(got["tensors"]["s3b2c"])[0])
 
 
 def test_cnn_run_matches_oracle_network(oracle):
