@@ -83,7 +83,7 @@ template <bool kVec, bool kTwo = false, bool kLean = false>
 __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
     const void* __restrict__ in, int in_is_i32, float alpha, long n, DevTable t,
     float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
-    uint16_t* __restrict__ dbg_seg)
+    uint16_t* __restrict__ dbg_seg, int streams)
 {
     extern __shared__ float2 s_kb[];
     // uniform tables sit in LDS as two arrays, k[] then b[]: consecutive segments then fall into
@@ -115,11 +115,13 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
         // one group of four elements: load, scale, PWL, requantise, store
         auto load_group = [&](long gidx, float (&x)[4]) {
             if (!kLean && in_is_i32) {
-                v4i a = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(in) + gidx);
+                const v4i* ptr = reinterpret_cast<const v4i*>(in) + gidx;
+                v4i a = streams ? __builtin_nontemporal_load(ptr) : *ptr;  // block-uniform choice
 #pragma unroll
                 for (int e = 0; e < 4; ++e) x[e] = (float)a[e] * alpha;
             } else {
-                v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(in) + gidx);
+                const v4f* ptr = reinterpret_cast<const v4f*>(in) + gidx;
+                v4f a = streams ? __builtin_nontemporal_load(ptr) : *ptr;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) x[e] = a[e] * alpha;
             }
@@ -181,7 +183,10 @@ __global__ __launch_bounds__(kRowThreads) void pwl_apply_kernel(
 // the end are then computed on a copy of the last row and only their stores are masked, so the
 // whole body is straight-line code: no per-element predicates, and the table look-ups of a row
 // are issued together instead of one per basic block.
-template <int G, int C, bool kI32, bool kVec, bool kFull>
+// kU (kFull only): rows a lane group handles per trip; their loads are all issued before the first
+// row is computed (more bytes in flight per lane; a block then covers kU * kRowsPerBlock consecutive
+// rows per trip).  kStream: loads marked non-temporal, for inputs too large to be cache-resident.
+template <int G, int C, bool kI32, bool kVec, bool kFull, int kU = 1, bool kStream = false>
 __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
     const void* __restrict__ in, float alpha, long rows, int cols, DevTable t_exp, DevTable t_recip,
     float out_inv_scale, int8_t* __restrict__ out_q, float* __restrict__ out_f32,
@@ -202,8 +207,26 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
     const float clo = t_exp.clamp_input ? t_exp.lo : -__builtin_inff();
     const float chi = t_exp.clamp_input ? t_exp.hi : __builtin_inff();
 
-    for (long row0 = (long)blockIdx.x * kRowsPerBlock; row0 < rows;
-         row0 += (long)gridDim.x * kRowsPerBlock) {
+    static_assert(kU == 1 || kFull, "several rows per trip: full rows only");
+    for (long row00 = (long)blockIdx.x * (kRowsPerBlock * kU); row00 < rows;
+         row00 += (long)gridDim.x * (kRowsPerBlock * kU)) {
+      v4i raw[kU][C];
+      if (kFull) {
+#pragma unroll
+        for (int ur = 0; ur < kU; ++ur) {
+            const long r = row00 + ur * kRowsPerBlock + sub;
+            const int* src = reinterpret_cast<const int*>(in) + (r < rows ? r : rows - 1) * (long)cols;
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const v4i* ptr = reinterpret_cast<const v4i*>(src + 4 * (g + G * c));
+                raw[ur][c] = kStream ? __builtin_nontemporal_load(ptr) : *ptr;
+            }
+        }
+      }
+#pragma unroll
+      for (int ur = 0; ur < kU; ++ur) {
+        const long row0 = row00 + ur * kRowsPerBlock;
+        if (ur > 0 && row0 >= rows) break;  // block-uniform
         const long row = row0 + sub;
         const bool live = row < rows;
         const long base = (kFull && !live ? rows - 1 : row) * (long)cols;
@@ -218,7 +241,13 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
             const int j0 = 4 * (g + G * c);
 #pragma unroll
             for (int q = 0; q < 4; ++q) ok[c][q] = kFull || (live && (j0 + q) < cols);
-            if (kVec) {
+            if (kFull) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (kI32) ai[c][q] = raw[ur][c][q];
+                    else e[c][q] = __int_as_float(raw[ur][c][q]);
+                }
+            } else if (kVec) {
                 if (ok[c][0]) {  // cols % 4 == 0: a group is all in or all out
                     if (kI32) {
                         v4i a = *reinterpret_cast<const v4i*>(reinterpret_cast<const int*>(in) + base + j0);
@@ -300,6 +329,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_pwl_kernel(
                     }
             }
         }
+      }
     }
 }
 
@@ -425,6 +455,15 @@ static int blocks_for(long units, int per_block, long cap_override = 0)
     return (int)b;
 }
 
+// Inputs beyond what the 256 MB last-level cache can hold take the streaming variant of the softmax
+// kernel (several rows per trip, non-temporal loads: +5 points of HBM peak on buffers that are not
+// cache-resident, -13 on ones that are); smaller ones were probably just written by the previous
+// kernel and are read through the caches.  (The same variant of LayerNorm measured no gain.)
+static bool streaming_input(long bytes) { return bytes >= (192L << 20); }
+
+// rows per trip of the streaming variants: about eight 16-byte loads in flight per lane
+constexpr int rows_per_trip(int C) { return C >= 8 ? 1 : C >= 3 ? 2 : C == 2 ? 4 : 8; }
+
 // Pick (G, C) so that G * 4 * C >= cols: G lanes per row, C groups per lane.
 struct RowShape { int G, C; };
 static RowShape row_shape(int cols)
@@ -446,10 +485,16 @@ static bool launch_softmax_t(RowShape rs, dim3 grid_hint, size_t shmem, hipStrea
                              uint16_t* sr)
 {
     (void)grid_hint;
+    const bool streams = streaming_input(rows * (long)cols * 4);
 #define NM_SM_CASE(GG, CC)                                                                          \
     if (rs.G == GG && rs.C == CC) {                                                                 \
         constexpr int rpb = (64 / GG) * (kRowThreads / 64);                                         \
-        if (kVec && cols == 4 * GG * CC)                                                            \
+        constexpr int ku = kVec ? rows_per_trip(CC) : 1;                                            \
+        if (kVec && cols == 4 * GG * CC && streams)                                                 \
+            hipLaunchKernelGGL((softmax_pwl_kernel<GG, CC, kI32, kVec, kVec, ku, kVec>),            \
+                               dim3(blocks_for(rows, rpb * ku)), dim3(kRowThreads), shmem, stream,  \
+                               in, alpha, rows, cols, te, tr, ois, oq, of, se, sr);                 \
+        else if (kVec && cols == 4 * GG * CC)                                                       \
             hipLaunchKernelGGL((softmax_pwl_kernel<GG, CC, kI32, kVec, kVec>),                      \
                                dim3(blocks_for(rows, rpb)), dim3(kRowThreads), shmem, stream, in,   \
                                alpha, rows, cols, te, tr, ois, oq, of, se, sr);                     \
@@ -568,7 +613,8 @@ int32_t nm_pwl_apply(const void* in, int32_t in_dtype, float alpha, int64_t n,
                            : blocks_for(n, kRowThreads);
     auto launch = [&](auto kern) {
         hipLaunchKernelGGL(kern, dim3(blocks), dim3(kRowThreads), shmem, (hipStream_t)stream, in,
-                           in_dtype == NM_DT_I32, alpha, (long)n, t, out_inv_scale, out_q, out_f32, dbg_seg);
+                           in_dtype == NM_DT_I32, alpha, (long)n, t, out_inv_scale, out_q, out_f32, dbg_seg,
+                           (int)streaming_input((long)n * 4));
     };
     const bool lean = vec && !two && in_dtype == NM_DT_F32 && out_q && !out_f32 && !dbg_seg;
     if (lean) launch(pwl_apply_kernel<true, false, true>);

@@ -349,6 +349,51 @@ def test_softmax_pwl_headline_shape_int8_only(oracle):
     assert_exact(host(oq), r["q"], "softmax int8 headline shape")
 
 
+@pytest.mark.parametrize("rows,cols,dtype", [(98304 + 5, 512, "i32"), (393216 + 3, 128, "i32"), (65536 + 1, 768, "f32")])
+def test_softmax_pwl_beyond_cache_sampled_rows(oracle, rows, cols, dtype):
+    """Inputs of 192 MB and more take the kernel's streaming variant (several rows per trip); the
+    row counts are ragged against every rows-per-trip value.  Rows are independent, so the oracle
+    computes a sample of them (the first and last 70 and 1500 random ones) from the same bytes."""
+    ot, dt = both_tables(oracle, [("exp", -16.0, 0.0, 128), ("recip", 1.0, float(max(64, cols)), 128)])
+    g = torch.Generator(device="cpu").manual_seed(rows + cols)
+    if dtype == "i32":
+        xd_host = torch.randint(-3000, 3000, (rows, cols), dtype=torch.int32, generator=g)
+        alpha = 3e-3
+    else:
+        xd_host = torch.randn((rows, cols), dtype=torch.float32, generator=g) * 3.0
+        alpha = 1.0
+    assert xd_host.numel() * 4 >= 192 << 20
+    oq = torch.full((rows + 1, cols), 99, dtype=torch.int8, device=DEV)
+    sr = torch.empty((rows,), dtype=torch.int16, device=DEV)
+    nm.nm_softmax_pwl(xd_host.to(DEV), alpha, dt, 0, 1, 127.0, out_q=oq, dbg_seg_recip=sr, rows=rows, cols=cols)
+    torch.cuda.synchronize()
+    pick = np.unique(np.concatenate([np.arange(70), np.arange(rows - 70, rows),
+                                     np.random.default_rng(1).integers(0, rows, 1500)]))
+    r = oracle.softmax_pwl(np.ascontiguousarray(xd_host.numpy()[pick]), alpha, ot[0], ot[1], 127.0)
+    got = oq.cpu().numpy()
+    assert_exact(got[pick], r["q"], f"softmax int8, sampled rows of {rows}x{cols}")
+    assert_exact(sr.cpu().numpy().view(np.uint16)[pick], r["seg_recip"], "softmax recip segments, sampled rows")
+    assert np.all(got[rows] == 99)   # nothing past the last row
+
+
+def test_pwl_apply_beyond_cache_sampled(oracle):
+    """2^26 + 3 fp32 values (the size the benchmark times, plus a ragged tail): streaming loads, one
+    32 KB span per block; the oracle evaluates a sample of positions and the whole tail."""
+    ot, dt = both_tables(oracle, SPECS[:1])
+    n = (1 << 26) + 3
+    g = torch.Generator(device="cpu").manual_seed(11)
+    x = torch.randn((n,), dtype=torch.float32, generator=g) * 3.0
+    oq = torch.full((n + 13,), 99, dtype=torch.int8, device=DEV)
+    nm.nm_pwl_apply(x.to(DEV), 1.0, dt, 0, 30.0, out_q=oq, n=n)
+    torch.cuda.synchronize()
+    pick = np.unique(np.concatenate([np.arange(9000), np.arange(n - 9000, n),
+                                     np.random.default_rng(2).integers(0, n, 200000)]))
+    _, q, _ = oracle.pwl_apply(np.ascontiguousarray(x.numpy()[pick]), ot[0], alpha=1.0, out_inv_scale=30.0)
+    got = oq.cpu().numpy()
+    assert_exact(got[pick], q, "pwl_apply int8, sampled positions of 2^26 + 3")
+    assert np.all(got[n:] == 99)
+
+
 # ---- LayerNorm-PWL ----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("rows,cols", [(37, 1), (37, 4), (37, 96), (101, 128), (37, 768), (9, 1000),
