@@ -120,6 +120,26 @@ def test_exact_mode_equals_library_transformer_layer(oracle, name):
     assert 1.0 <= obs["softmax_den_max"] <= cfg["S"]
 
 
+def test_stack_is_the_layers_one_after_the_other(oracle):
+    """encoder_stack against the pinned single layer: a stack of one layer is that layer; a stack of
+    three distinct layers ends where feeding each layer's int8 output to the next one by hand ends
+    (and not where the layers in another order, or the first input fed to every layer, end)."""
+    stack = W.stack_params("tiny", 3)
+    tables = make_tables(oracle, W.config("tiny"))
+    x = stack[0]["x"]
+    one = oracle.encoder_stack(stack[:1], tables, x)
+    assert np.array_equal(one["y_q"], oracle.encoder_layer(stack[0], tables, x)["y_q"])
+    by_hand = x
+    for p in stack:
+        by_hand = oracle.encoder_layer(p, tables, by_hand, want_taps=False)["y_q"]
+    got = oracle.encoder_stack(stack, tables, x)
+    assert np.array_equal(got["y_q"], by_hand)
+    assert got["y_q"].dtype == np.int8 and got["y_q"].shape == x.shape
+    swapped = oracle.encoder_stack([stack[1], stack[0], stack[2]], tables, x)["y_q"]
+    unchained = oracle.encoder_layer(stack[2], tables, x, want_taps=False)["y_q"]
+    assert not np.array_equal(got["y_q"], swapped) and not np.array_equal(got["y_q"], unchained)
+
+
 def test_stored_scales_are_the_calibration_output(oracle):
     """The stored scale file is what the calibration run of the exact-function layer produces."""
     from oracle import make_scales
