@@ -604,6 +604,43 @@ def test_gemm_headline_ffn1_sampled(oracle):
     assert_exact(host(oq)[rows], r["q"], "FFN1 sampled rows")
 
 
+@pytest.mark.parametrize("M,N,K,split,what", [
+    (8192, 3072, 768, 0, "two rounds of tiles"), (8192, 2304, 768, 768, "QKV: one scale per column third, 1.5 rounds"),
+    (16384, 4096, 1024, 0, "5.5 rounds, last column tile partly outside"),
+    (7977, 3000 + 8, 768, 0, "ragged rows and columns"), (768, 8 * 192 * 16 + 16, 1024, 0, "three tile rows, a tile count that is no multiple of 8")])
+def test_gemm_more_tiles_than_compute_units_sampled(oracle, M, N, K, split, what):
+    """The QKV / FFN1 shapes of the 512-token workloads (several rounds of 256 x 192 tiles over the
+    256 compute units; XCD-aware tile order with and without a tile count that divides by 8): int8
+    output with the table, and without it (with one inverse scale per column third where given).  The
+    oracle computes 96 sampled rows, among them the first and last of the matrix and rows around tile
+    edges."""
+    ot, dt = both_tables(oracle, [("gelu", -8.0, 8.0, 128)])
+    d = W.gemm_inputs(M, N, K, seed=M + N + K, full_range=False)
+    alpha = float(np.float32(6.0 / (20 * 20 * np.sqrt(K))))
+    dA, dW, db = dev(d["A"]), dev(d["W"]), dev(d["bias"])
+    g = np.random.default_rng(M)
+    edge = [r for r in (0, 1, 31, 32, 63, 64, 255, 256, 257, 511, 512, M - 257, M - 256, M - 65, M - 2, M - 1) if 0 <= r < M]
+    rows = np.unique(np.concatenate([np.array(edge), g.choice(M, 96 - len(edge), replace=False)]))
+    A_s = np.ascontiguousarray(d["A"][rows])
+    oq = torch.full((M + 1, N), 77, dtype=torch.int8, device=DEV)
+    nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, tables=dt, table_idx=0, out_inv_scale=25.0, out_q=oq, M=M)
+    r = oracle.gemm_pwl(A_s, d["W"], bias=d["bias"], alpha=alpha, table=ot[0], out_inv_scale=25.0)
+    got = host(oq)
+    assert_exact(got[rows], r["q"], f"int8 + table: {what}")
+    assert np.all(got[M] == 77)
+    if split:
+        inv3 = (40.0, 23.0, 31.0)
+        nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, split_cols=split, out_inv_scale3=inv3, out_q=oq, M=M)
+        want = np.concatenate([oracle.gemm_pwl(A_s, d["W"][t * split:(t + 1) * split], bias=d["bias"][t * split:(t + 1) * split],
+                                               alpha=alpha, out_inv_scale=inv3[t])["q"] for t in range(3)], axis=1)
+    else:
+        nm.nm_gemm_pwl(dA, dW, bias=db, alpha=alpha, out_inv_scale=40.0, out_q=oq, M=M)
+        want = oracle.gemm_pwl(A_s, d["W"], bias=d["bias"], alpha=alpha, out_inv_scale=40.0)["q"]
+    got = host(oq)
+    assert_exact(got[rows], want, f"int8: {what}")
+    assert np.all(got[M] == 77)
+
+
 # ---- attention products -----------------------------------------------------------------------
 
 @pytest.mark.parametrize("B,S,H,heads", [(1, 64, 128, 2), (3, 40, 96, 3), (2, 128, 768, 12), (1, 200, 64, 1),
