@@ -918,7 +918,12 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     }
     const bool stream_ok = al && !g.w_is_kn && g.K % 64 == 0 && !force_generic();
     // the tile kernel: plain matrix products with the encoder layer's epilogues
-    const bool tile_epi = (epi == EPI_Q || epi == EPI_Q_TABLE) ? p.q16 != 0
+    // int8 output through a merged table kept in two levels: the tile kernel has an epilogue for it
+    // (elsewhere the generic one looks it up)
+    const bool two_level_q = g.has_table && g.table.cellmap && !g.table.clamp_input && g.out_q && !g.out_f32 &&
+                             !g.out_acc && !g.resid && !g.out_inv_scale_vec && !g.dbg_seg && g.table.nkb <= 256 &&
+                             g.table.nseg <= 1024;
+    const bool tile_epi = (epi == EPI_Q || epi == EPI_Q_TABLE || two_level_q) ? p.q16 != 0
                         : epi == EPI_F32_RESID ? (p.r16 != 0 && aligned(g.out_f32, 16) && g.ldo % 4 == 0) : false;
     const bool tile_ok = stream_ok && tile_epi && batches == 1 && g.K % 128 == 0 && g.K / 128 >= 3 && !g.alpha_vec &&
                          g.N % 16 == 0 && g.split_cols % 4 == 0 && (int64_t)g.M * g.lda < (1LL << 32) &&
@@ -945,6 +950,7 @@ int32_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     } else if (tile_ok && !old_big && forced_cfg() == 0 && g.K / 128 >= 3) {
         tile_cfg = 0;
     }
+    if (tile_cfg >= 0 && two_level_q) epi = EPI_Q_TABLE2;
     if (tile_cfg == 0) {
         rc = launch_tile<256, 192, 4, 2, 2>(p, epi, table_bytes, stream);
     } else if (tile_cfg == 1) {

@@ -59,7 +59,9 @@ __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >>
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * kBK + ((chunk ^ swz(row)) << 4); }
 
 
-enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4, EPI_Q_TABLE_RESID = 5, EPI_F32_RESID_LN = 6 };
+enum { EPI_GENERIC = 0, EPI_Q = 1, EPI_Q_TABLE = 2, EPI_F32_RESID = 3, EPI_ACC = 4, EPI_Q_TABLE_RESID = 5, EPI_F32_RESID_LN = 6, EPI_Q_TABLE2 = 7 };
+// EPI_Q_TABLE2: EPI_Q_TABLE for a merged table in its two-level form (one byte per primary cell naming the
+// merged segment, one {k, b} per merged segment; tile kernel only).
 // EPI_F32_RESID_LN: EPI_F32_RESID followed by LayerNorm-PWL over the row, inside the kernel: the tile
 // covers whole rows (tile kernel only).
 // EPI_Q_TABLE_RESID: int8 residual, table (no input clamp), int8 output: the last convolution of a

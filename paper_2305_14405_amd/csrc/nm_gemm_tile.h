@@ -54,7 +54,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
     constexpr int DPS = (LB + POST + NMF - 1) / (POST + NMF);  // refill loads per slot (those slots and the next k-step's)
     static_assert(ROWS % RPI == 0 && BM % RPI == 0, "whole blocks");
     static_assert(TM >= 2 && TN >= 2 && KS % 2 == 0, "wavefront tile");
-    static_assert(kEpi == EPI_Q || kEpi == EPI_Q_TABLE || kEpi == EPI_F32_RESID || kEpi == EPI_F32_RESID_LN,
+    constexpr bool kTable = kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE2;
+    static_assert(kEpi == EPI_Q || kTable || kEpi == EPI_F32_RESID || kEpi == EPI_F32_RESID_LN,
                   "epilogues of the tile kernel");
     static_assert(kEpi != EPI_F32_RESID_LN || WAVES_M == 1, "row statistics: a wavefront holds all rows of its columns");
     constexpr bool kResid = kEpi == EPI_F32_RESID || kEpi == EPI_F32_RESID_LN;
@@ -124,6 +125,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
             const int e = tid + t * 64 * NW;
             kb_reg[t] = e < p.table.nseg ? p.table.kb[e] : make_float2(0.0f, 0.0f);
         }
+    }
+    // two-level form: at most 256 merged segments and 256 cells (host), i.e. one {k, b} pair and one
+    // word of four cell bytes per thread at most
+    unsigned map_reg = 0;
+    if (kEpi == EPI_Q_TABLE2) {
+        kb_reg[0] = tid < p.table.nkb ? p.table.ckb[tid] : make_float2(0.0f, 0.0f);
+        if (tid < (p.table.nseg + 3) / 4) map_reg = reinterpret_cast<const unsigned*>(p.table.cellmap)[tid];
     }
 
     // the int8 residual tile (fp32 epilogue) as 16-byte row pieces
@@ -248,6 +256,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
         }
         for (int e = tid + KPT * 64 * NW; e < p.table.nseg; e += 64 * NW) s_kb[e] = p.table.kb[e];
     }
+    const uint8_t* s_map = reinterpret_cast<const uint8_t*>(s_kb + p.table.nkb);  // cell -> merged segment
+    if (kEpi == EPI_Q_TABLE2) {
+        if (tid < p.table.nkb) s_kb[tid] = kb_reg[0];
+        if (tid < (p.table.nseg + 3) / 4) reinterpret_cast<unsigned*>(s_kb + p.table.nkb)[tid] = map_reg;
+    }
     constexpr int RW = BN + 16;  // row stride of the residual image
     int8_t* s_res = smem;        // in the ring, which is free now
     if (kResid) {
@@ -268,7 +281,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
 #pragma unroll
         for (int g = 0; g < 4; ++g) bi[j][g] = *reinterpret_cast<const v4f*>(s_bias + wave_n + 32 * j + 8 * g + 4 * frag_half);
     constexpr int NG = TM * TN * 4;  // groups of four columns per lane
-    if constexpr (kEpi == EPI_Q_TABLE || kEpi == EPI_Q) {
+    if constexpr (kTable || kEpi == EPI_Q) {
         constexpr int SW = WN + 16;
         static_assert(NW * WM * SW <= STAGES * STAGE_BYTES, "patch fits the ring");
         int8_t* patch = smem + wave * (WM * SW);
@@ -289,16 +302,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
         // group index -> (i, j, g), i innermost: consecutive groups use different accumulators
         auto stage_a = [&](int G) {
             const int i = G % TM, jg = G / TM, j = jg / 4, g = jg % 4;
+            unsigned cellv[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float v = __builtin_fmaf((float)acc[i][j][4 * g + e], alpha, bi[j][g][e]);
                 x[G % (DEPTH + 1)][e] = v;
-                if (kEpi == EPI_Q_TABLE) {  // segment of v (subtract, multiply, clamp in float, floor)
+                if (kTable) {  // segment of v (subtract, multiply, clamp in float, floor)
                     float u = v - tlo;
                     u = u * tiw;
                     u = __builtin_amdgcn_fmed3f(u, 0.0f, tmax);
-                    kb[G % (DEPTH + 1)][e] = s_kb[(int)u];
+                    if (kEpi == EPI_Q_TABLE2) cellv[e] = s_map[(int)u];
+                    else kb[G % (DEPTH + 1)][e] = s_kb[(int)u];
                 }
+            }
+            if (kEpi == EPI_Q_TABLE2) {  // second level: the four cell bytes have been requested together
+#pragma unroll
+                for (int e = 0; e < 4; ++e) kb[G % (DEPTH + 1)][e] = s_kb[cellv[e]];
             }
         };
         auto stage_b = [&](int G) {
@@ -307,7 +326,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 1) void gemm_tile_kernel(Ge
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float v = x[G % (DEPTH + 1)][e];
-                if (kEpi == EPI_Q_TABLE) v = __builtin_fmaf(kb[G % (DEPTH + 1)][e].x, v, kb[G % (DEPTH + 1)][e].y);
+                if (kTable) v = __builtin_fmaf(kb[G % (DEPTH + 1)][e].x, v, kb[G % (DEPTH + 1)][e].y);
                 q[e] = requant(v, inv_g[j][g]);
             }
             *reinterpret_cast<unsigned*>(patch + (32 * i + frag_row) * SW + 32 * j + 8 * g + 4 * frag_half) =
@@ -513,6 +532,7 @@ static int32_t launch_tile(GemmParams& p, int epi, size_t table_bytes, hipStream
     switch (epi) {
     case EPI_Q: return launch_tile_epi<BM, BN, WAVES_M, WAVES_N, STAGES, EPI_Q>(p, table_bytes, s);
     case EPI_Q_TABLE: return launch_tile_epi<BM, BN, WAVES_M, WAVES_N, STAGES, EPI_Q_TABLE>(p, table_bytes, s);
+    case EPI_Q_TABLE2: return launch_tile_epi<BM, BN, WAVES_M, WAVES_N, STAGES, EPI_Q_TABLE2>(p, table_bytes, s);
     default: return launch_tile_epi<BM, BN, WAVES_M, WAVES_N, STAGES, EPI_F32_RESID>(p, table_bytes, s);
     }
 }

@@ -132,7 +132,9 @@ int32_t nm_encoder_layer(const nm_layer_desc* d, const int8_t* x, int8_t* y_q, f
     if (!d->Wqkv || !d->Wo || !d->W1 || !d->W2 || !d->gamma1 || !d->beta1 || !d->gamma2 || !d->beta2)
         return fail(NM_ERR_INVALID_ARG, "nm_encoder_layer: NULL weight or LayerNorm vector");
     DevTable t_gelu, t_exp, t_recip, t_rsqrt;
-    if ((rc = get_dev_table(d->tables, d->gelu_idx, &t_gelu, "nm_encoder_layer(gelu)"))) return rc;
+    // the GELU table in its two-level form where it has one (FFN1's epilogue looks it up that way);
+    // the row kernels and the attention kernel read the expanded form of theirs
+    if ((rc = get_dev_table(d->tables, d->gelu_idx, &t_gelu, "nm_encoder_layer(gelu)", true))) return rc;
     if ((rc = get_dev_table(d->tables, d->exp_idx, &t_exp, "nm_encoder_layer(exp)"))) return rc;
     if ((rc = get_dev_table(d->tables, d->recip_idx, &t_recip, "nm_encoder_layer(recip)"))) return rc;
     if ((rc = get_dev_table(d->tables, d->rsqrt_idx, &t_rsqrt, "nm_encoder_layer(rsqrt)"))) return rc;

@@ -128,7 +128,8 @@ def test_clamp_input_flag(oracle):
 ELASTIC = [("bias", nm.NM_TABLE_BIAS_CORRECT, 0.0, 0.0),
            ("bias_threshold", nm.NM_TABLE_BIAS_CORRECT, 2e-3, 0.0),
            ("merge", nm.NM_TABLE_MERGE, 0.0, 0.02),
-           ("merge_bias", nm.NM_TABLE_MERGE | nm.NM_TABLE_BIAS_CORRECT, 0.0, 0.02)]
+           ("merge_bias", nm.NM_TABLE_MERGE | nm.NM_TABLE_BIAS_CORRECT, 0.0, 0.02),
+           ("merge_two_level", nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT, 0.0, 0.02)]
 
 
 def elastic_tables(oracle, specs, flags, e_th, dk_th):
@@ -143,7 +144,10 @@ def elastic_tables(oracle, specs, flags, e_th, dk_th):
         else:
             t = oracle.build_table(OID[f], lo, hi, n, flags=oflags, e_th=e_th)
         ot.append(t)
-    injected = nm.nm_tables_from_arrays([(f, lo, hi, n, 0) for (f, lo, hi, n) in specs],
+    # injected arrays are the expanded form; with the two-level flag the library folds them back into
+    # runs of equal lines (the same values, looked up through the cell map)
+    iflags = (nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT) if flags & nm.NM_TABLE_COMPACT else 0
+    injected = nm.nm_tables_from_arrays([(f, lo, hi, n, iflags) for (f, lo, hi, n) in specs],
                                         [t.k for t in ot], [t.b for t in ot])
     built = nm.nm_build_tables([(f, lo, hi, n, flags, e_th, dk_th) for (f, lo, hi, n) in specs])
     return ot, injected, built
@@ -218,6 +222,17 @@ def test_elastic_tables_encoder_layer(oracle, label, flags, e_th, dk_th):
     assert np.allclose(got["y_f32"], want["y_f32"], rtol=1e-4, atol=1e-5)
 
 
+def test_encoder_layer_two_level_gelu_table_headline_shape(oracle):
+    """The headline layer with merged tables in the two-level form: FFN1 looks its GELU table up in
+    two levels inside the large-tile kernel (the other kernels read the expanded form); every stage
+    equals the oracle's layer on the same merged tables."""
+    want, got = run_layer(oracle, "bert_base_layer", elastic=(nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT, 0.0, 0.01))
+    for k in ("qkv", "ctx", "ln1", "ffn1", "y_q"):
+        assert_exact(got[k], want[k], f"two-level tables, headline layer {k}")
+    for k in ("attn", "ffn2", "y_f32"):
+        assert_f32_close(got[k], want[k], f"two-level tables, headline layer {k}")
+
+
 # ---- merged tables looked up in two levels (cell of x, merged segment of the cell) ------------
 
 @pytest.mark.parametrize("name,lo,hi,nprim,dk", [("gelu", -4.0, 4.0, 16, 0.1), ("gelu", -8.0, 8.0, 256, 0.01),
@@ -288,6 +303,32 @@ def test_two_level_table_gemm_epilogue(oracle, M, N, K):
     nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=dt, table_idx=0,
                    out_inv_scale=25.0, out_q=oq2)
     assert_exact(host(oq2).ravel(), q, "two-level gemm: int8 only")
+    assert len(np.unique(s)) > 5
+
+
+@pytest.mark.parametrize("M,N,K,nprim,dk", [(4096, 3072, 768, 128, 0.01), (3900, 784, 512, 256, 0.001), (8192, 1024, 512, 1024, 0.002)])
+def test_two_level_table_in_the_tile_kernel_sampled(oracle, M, N, K, nprim, dk):
+    """int8 output through a two-level GELU table at shapes the large-tile kernel takes (256 x 192,
+    128 x 128 with ragged edges, 256 x 128; up to 1024 primary cells): its own epilogue looks the cell
+    byte up first and the merged segment's line second.  The oracle computes 64 sampled rows: its GEMM,
+    then its direct evaluation of the merged table."""
+    lo, hi = -8.0, 8.0
+    mt = oracle.build_table_merged_direct(OID["gelu"], lo, hi, nprim, dk)
+    te, _ = oracle.build_table_merged(OID["gelu"], lo, hi, nprim, dk)
+    assert mt.nseg <= 256
+    dt = nm.nm_tables_from_arrays([("gelu", lo, hi, nprim, nm.NM_TABLE_MERGE | nm.NM_TABLE_COMPACT)], [te.k], [te.b])
+    d = W.gemm_inputs(M, N, K, seed=M + K + 3, full_range=False)
+    alpha = float(np.float32(9.0 / (20 * 20 * np.sqrt(K))))
+    rows = np.unique(np.concatenate([np.array([0, 1, 127, 128, 255, 256, M - 129, M - 2, M - 1]),
+                                     np.random.default_rng(M).choice(M, 55, replace=False)]))
+    pre = oracle.gemm_pwl(np.ascontiguousarray(d["A"][rows]), d["W"], bias=d["bias"], alpha=alpha)["y"]
+    y, q, s, c = oracle.pwl_apply_merged(pre.ravel(), mt, out_inv_scale=25.0)
+    oq = torch.full((M + 1, N), 77, dtype=torch.int8, device=DEV)
+    nm.nm_gemm_pwl(dev(d["A"]), dev(d["W"]), bias=dev(d["bias"]), alpha=alpha, tables=dt, table_idx=0,
+                   out_inv_scale=25.0, out_q=oq, M=M)
+    got = host(oq)
+    assert_exact(got[rows].ravel(), q, f"two-level table, tile kernel, {nprim} cells -> {mt.nseg} segments")
+    assert np.all(got[M] == 77)
     assert len(np.unique(s)) > 5
 
 
