@@ -96,16 +96,22 @@ def test_maxpool(oracle, B, H, W, Cc, k, stride, pad):
     assert np.array_equal(host(y), want)
 
 
-def test_avgpool(oracle):
-    x = rand_i8(np.random.default_rng(5), (5, 49, 2048))
-    alpha = float(np.float32(0.013 / 49))
+@pytest.mark.parametrize("B,HW,C", [(5, 49, 2048), (3, 10, 30), (2, 64, 12), (64, 49, 2048), (1, 1, 4)])
+def test_avgpool(oracle, B, HW, C):
+    """Global average pooling: four channels per thread where C allows, one otherwise; position counts
+    with and without a tail behind the groups of eight."""
+    x = rand_i8(np.random.default_rng(B + HW + C), (B, HW, C))
+    alpha = float(np.float32(0.013 / HW))
     want = oracle.avgpool_i8(x, alpha, 55.0)
-    q = torch.empty((5, 2048), dtype=torch.int8, device=DEV)
-    f = torch.empty((5, 2048), dtype=torch.float32, device=DEV)
+    q = torch.full((B + 1, C), 77, dtype=torch.int8, device=DEV)
+    f = torch.empty((B, C), dtype=torch.float32, device=DEV)
     dx = dev(x)
     nm.nm_avgpool_i8(dx, alpha, 55.0, out_q=q, out_f32=f)
     assert np.array_equal(host(f).view(np.uint32), want["y"].view(np.uint32))
-    assert np.array_equal(host(q), want["q"])
+    assert np.array_equal(host(q)[:B], want["q"]) and np.all(host(q)[B] == 77)
+    q2 = torch.empty((B, C), dtype=torch.int8, device=DEV)
+    nm.nm_avgpool_i8(dx, alpha, 55.0, out_q=q2)     # int8 output alone
+    assert np.array_equal(host(q2), want["q"])
 
 
 def test_conv_validation_and_empty():
