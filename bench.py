@@ -113,9 +113,12 @@ def main():
         for name in args.also.split(","):
             a = argparse.Namespace(**vars(args))
             a.workload, a.steps, a.warmup, a.kernel_reps, a.brief = name, 10, 2, 10, True
-            o = run_workload(a)
-            others.append({k: o[k] for k in ("value", "unit", "ms_per_step", "steps", "config", "roofline",
-                                             "cpu_baseline", "parity")})
+            try:   # a problem in a side measurement must not cost the run its headline line
+                o = run_workload(a)
+                others.append({k: o[k] for k in ("value", "unit", "ms_per_step", "steps", "config", "roofline",
+                                                 "cpu_baseline", "parity")})
+            except Exception as e:  # noqa: BLE001
+                others.append(dict(config=dict(workload=name), error=f"{type(e).__name__}: {e}"))
         out["other_workloads"] = others
     print(json.dumps(out))
 
