@@ -68,10 +68,11 @@ enum {
     NM_TABLE_COMPACT = 8       /* keep a merged table in two levels as well: one {k, b} per merged
                                   segment plus one byte per primary cell naming its segment (at most
                                   256 segments), so that a kernel holds n_segments * 8 + nseg bytes of
-                                  it instead of nseg * 8.  nm_pwl_apply and nm_gemm_pwl look such a
-                                  table up in two steps (cell of x, segment of the cell); the other
-                                  entry points use its expanded form.  Results are identical either
-                                  way; reported segment indices are always primary cell indices */
+                                  it instead of nseg * 8.  nm_pwl_apply, nm_gemm_pwl and the FFN1
+                                  product of nm_encoder_layer / nm_encoder_stack look such a table up
+                                  in two steps (cell of x, segment of the cell); the other entry
+                                  points use its expanded form.  Results are identical either way;
+                                  reported segment indices are always primary cell indices */
 };
 
 enum { NM_DT_I32 = 0, NM_DT_F32 = 1 };
