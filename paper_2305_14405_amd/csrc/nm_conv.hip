@@ -10,6 +10,8 @@
 //  * anything else (the 3-channel stem, odd channel counts): a small kernel writes the patch
 //    matrix [B*Ho*Wo, K16] (K rounded up to 64, zero filled) into the caller's workspace and the
 //    GEMM runs on it.
+#include <type_traits>
+
 #include "nm_device.h"
 
 namespace nm {
@@ -287,24 +289,31 @@ __global__ __launch_bounds__(256) void stem_conv_kernel(StemParams p)
 
     // epilogue: lane (m, half) holds, per group g of four registers, channels 32j + 8g + 4half .. +3
     int8_t* patch = sO + wave * (64 * 80);
+    // (twice: a table of two segments, ReLU, is evaluated with a compare instead of index and gather)
+    auto finish = [&](auto two_c) {
+        constexpr bool kTwoSeg = decltype(two_c)::value;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = 32 * j + 8 * g + 4 * half;
-                const v4f sc = *reinterpret_cast<const v4f*>(s_cols + n);
-                const v4f bi = *reinterpret_cast<const v4f*>(s_cols + 64 + n);
-                int q[4];
+                for (int g = 0; g < 4; ++g) {
+                    const int n = 32 * j + 8 * g + 4 * half;
+                    const v4f sc = *reinterpret_cast<const v4f*>(s_cols + n);
+                    const v4f bi = *reinterpret_cast<const v4f*>(s_cols + 64 + n);
+                    int q[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float v = __builtin_fmaf((float)acc[t][j][4 * g + e], sc[e], bi[e]);
-                    if (p.has_table) { int sg; v = pwl_eval(v, p.table, s_kb, sg); }
-                    q[e] = requant(v, p.out_inv_scale);
+                    for (int e = 0; e < 4; ++e) {
+                        float v = __builtin_fmaf((float)acc[t][j][4 * g + e], sc[e], bi[e]);
+                        if (kTwoSeg) v = pwl_eval_two_segments(v, p.table);
+                        else if (p.has_table) { int sg; v = pwl_eval(v, p.table, s_kb, sg); }
+                        q[e] = requant(v, p.out_inv_scale);
+                    }
+                    *reinterpret_cast<unsigned*>(patch + (32 * t + fr) * 80 + n) = pack4(q[0], q[1], q[2], q[3]);
                 }
-                *reinterpret_cast<unsigned*>(patch + (32 * t + fr) * 80 + n) = pack4(q[0], q[1], q[2], q[3]);
-            }
+    };
+    if (p.has_table && p.table.two_seg) finish(std::true_type{});
+    else finish(std::false_type{});
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");

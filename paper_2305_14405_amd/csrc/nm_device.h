@@ -63,6 +63,15 @@ __device__ __forceinline__ float pwl_eval_noclamp(float x, const DevTable& t, co
     return __builtin_fmaf(e.x, x, e.y);
 }
 
+// A table of two segments (no clamp flag): both lines, and a compare against the smallest value of
+// segment 1 (found on the host with the index arithmetic itself) instead of index, gather and one
+// line.  The same value as pwl_eval_noclamp for every x, NaN and infinities included.
+__device__ __forceinline__ float pwl_eval_two_segments(float x, const DevTable& t)
+{
+    const float y0 = __builtin_fmaf(t.k0, x, t.b0), y1 = __builtin_fmaf(t.k1, x, t.b1);
+    return x >= t.tau ? y1 : y0;
+}
+
 // Symmetric int8 code: round-to-nearest-even of v * inv_scale, saturated to [-127, 127].
 // Returns a word whose LOW BYTE is the code (the other bytes are not meaningful): saturate first
 // (the bounds are integers and rounding is monotone, so clamp and round commute), then add

@@ -145,7 +145,8 @@ __device__ __forceinline__ void load_resid4(const GemmParams& p, long rowoff, in
 }
 
 // The arithmetic of the epilogue for four columns of one row (no global memory access).
-template <int kEpi>
+// kTwoSeg: the table has two segments and is evaluated with a compare (specialised table epilogues)
+template <int kEpi, bool kTwoSeg = false>
 __device__ __forceinline__ void epi_math(const GemmParams& p, const float2* s_kb, const int (&a4)[4],
                                          const Col4& c, const int (&r4)[4], Epi4& o)
 {
@@ -161,7 +162,8 @@ __device__ __forceinline__ void epi_math(const GemmParams& p, const float2* s_kb
         float v = __builtin_fmaf((float)a4[e], c.scale[e], c.bias[e]);
         if (use_resid) v = __builtin_fmaf((float)r4[e], rs, v);
         if (use_table) {
-            if (kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID) v = pwl_eval_noclamp(v, p.table, s_kb, o.s[e]);
+            if (kTwoSeg) v = pwl_eval_two_segments(v, p.table);
+            else if (kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID) v = pwl_eval_noclamp(v, p.table, s_kb, o.s[e]);
             else if (p.table.cellmap) v = pwl_eval_two_level(v, p.table, s_kb, o.s[e]);  // merged table, two steps
             else v = pwl_eval(v, p.table, s_kb, o.s[e]);
         }
@@ -662,8 +664,9 @@ void gemm_stream_kernel(GemmParams p)
     // The body exists twice: for a tile that lies wholly inside the output (and vector-aligned
     // outputs) every bounds test is a compile-time constant, which leaves straight-line code whose
     // table look-ups the scheduler can batch; edge tiles take the guarded copy.
-    auto finish_rows = [&](auto full_c) {
+    auto finish_rows = [&](auto full_c, auto two_c) {
         constexpr bool kFullTile = decltype(full_c)::value;
+        constexpr bool kTwoSeg = decltype(two_c)::value;   // two-segment table: compare instead of gather
 #pragma unroll
         for (int i = 0; i < TMF; ++i) {
             const int prow = 32 * (row_blk0 + i) + frag_row;  // row inside the sub-tile
@@ -700,7 +703,7 @@ void gemm_stream_kernel(GemmParams p)
                         load_resid4(p, rowoff, nb, vec, r4);
                     }
                     Epi4 o;
-                    epi_math<kEpi>(p, s_kb, a4, c, r4, o);
+                    epi_math<kEpi, kTwoSeg>(p, s_kb, a4, c, r4, o);
                     epi_store<kEpi>(p, rowoff, nb, a4, o, vec, patch_q);
                     if (patch_q)
                         *reinterpret_cast<unsigned*>(patch + prow * SW + 32 * j + 8 * g + 4 * frag_half) =
@@ -730,8 +733,13 @@ void gemm_stream_kernel(GemmParams p)
             }
         }
     };
-    if (m0 + BM <= p.M && n0 + BN <= p.N && p.vec_out) finish_rows(std::true_type{});
-    else finish_rows(std::false_type{});
+    constexpr bool kTableEpi = kEpi == EPI_Q_TABLE || kEpi == EPI_Q_TABLE_RESID;
+    if (m0 + BM <= p.M && n0 + BN <= p.N && p.vec_out) {
+        if (kTableEpi && p.table.two_seg) finish_rows(std::true_type{}, std::integral_constant<bool, kTableEpi>{});
+        else finish_rows(std::true_type{}, std::false_type{});
+    } else {
+        finish_rows(std::false_type{}, std::false_type{});
+    }
 }
 
 template <int BM, int BN, int WM, int WN>

@@ -23,6 +23,10 @@ struct DevTable {
     const float2* ckb;
     const uint8_t* cellmap;
     int nkb;
+    // a table of two segments (without the clamp flag): its two lines and the smallest fp32 value
+    // whose segment index is 1, so that a kernel may pick the line with one compare (two_seg != 0)
+    int two_seg;
+    float k0, b0, k1, b1, tau;
 };
 
 struct HostTable {

@@ -7,6 +7,7 @@
 // merged first (Algorithm 2).  Everything is computed in binary64 and rounded once to binary32.
 #include <cmath>
 #include <cstring>
+#include <limits>
 #include <new>
 
 #include "nm_internal.h"
@@ -38,6 +39,41 @@ int32_t check_hip(hipError_t e, const char* what)
     return fail(NM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// The smallest fp32 x whose segment index in a two-segment table is 1, i.e. for which the kernels'
+// index arithmetic, u = (x - lo) * inv_w in fp32 (one subtract, one multiply), gives u >= 1.  Both
+// operations round monotonically and inv_w > 0, so the set is an upper interval of the floats and
+// bisection over their order finds its first element (+inf if there is none).  x >= tau then decides
+// exactly what the index computation decides, for every x (a NaN compares false: segment 0, as there).
+static float two_segment_threshold(float lo, float inv_w)
+{
+    auto in_upper = [&](float x) {
+        volatile float u = x - lo;
+        u = u * inv_w;
+        return u >= 1.0f;
+    };
+    // floats in increasing order <-> unsigned keys in increasing order
+    auto to_float = [](uint32_t key) {
+        const uint32_t bits = (key & 0x80000000u) ? key ^ 0x80000000u : ~key;
+        float f;
+        std::memcpy(&f, &bits, sizeof f);
+        return f;
+    };
+    auto to_key = [](float f) {
+        uint32_t bits;
+        std::memcpy(&bits, &f, sizeof bits);
+        return (bits & 0x80000000u) ? ~bits : bits ^ 0x80000000u;
+    };
+    const float big = std::numeric_limits<float>::max();
+    if (!in_upper(big)) return std::numeric_limits<float>::infinity();
+    if (in_upper(-big)) return -big;
+    uint32_t a = to_key(-big), b = to_key(big);   // in_upper(a) false, in_upper(b) true
+    while (b - a > 1) {
+        const uint32_t mid = a + (b - a) / 2;
+        if (in_upper(to_float(mid))) b = mid; else a = mid;
+    }
+    return to_float(b);
+}
+
 int32_t get_dev_table(const nm_tables* t, int32_t idx, DevTable* dt, const char* what, bool two_level)
 {
     if (!t) return fail(NM_ERR_INVALID_ARG, "%s: tables is NULL", what);
@@ -52,6 +88,12 @@ int32_t get_dev_table(const nm_tables* t, int32_t idx, DevTable* dt, const char*
     dt->nseg = h.desc.nseg;
     dt->clamp_input = (h.desc.flags & NM_TABLE_CLAMP_INPUT) ? 1 : 0;
     dt->ckb = nullptr; dt->cellmap = nullptr; dt->nkb = 0;
+    dt->two_seg = 0; dt->k0 = dt->b0 = dt->k1 = dt->b1 = dt->tau = 0.0f;
+    if (h.desc.nseg == 2 && !dt->clamp_input) {
+        dt->two_seg = 1;
+        dt->k0 = h.k[0]; dt->b0 = h.b[0]; dt->k1 = h.k[1]; dt->b1 = h.b[1];
+        dt->tau = two_segment_threshold(h.desc.lo, h.inv_w);
+    }
     if (two_level && !h.cellmap.empty()) {
         dt->ckb = t->d_blob + h.cblob_offset;
         dt->cellmap = reinterpret_cast<const uint8_t*>(t->d_blob + h.map_offset);

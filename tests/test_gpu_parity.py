@@ -682,6 +682,49 @@ def test_gemm_more_tiles_than_compute_units_sampled(oracle, M, N, K, split, what
     assert np.all(got[M] == 77)
 
 
+@pytest.mark.parametrize("lo,hi", [(-8.0, 8.0), (-1.0, 3.0), (-6.0, 2.5)])
+def test_two_segment_table_is_decided_by_one_compare_exactly(oracle, lo, hi):
+    """A table of two segments (ReLU in the CNN) is evaluated in the matrix product's epilogue with a
+    compare against the smallest value of segment 1 instead of index and gather.  With zero operands the
+    pre-activation of column n is bias[n] exactly, so the bias vector sweeps the neighbourhood of the
+    break point float by float (and zeros, denormals, infinities, NaN); a huge output scale makes the
+    int8 code tell a tiny negative from zero.  Every code equals the oracle's, which indexes the table."""
+    ot, dt = both_tables(oracle, [("relu", lo, hi, 2)])
+    mid = np.float32((lo + hi) / 2)
+    around = [mid]
+    for _ in range(300):
+        around.append(np.nextafter(around[-1], np.float32(np.inf), dtype=np.float32))
+    down = [mid]
+    for _ in range(300):
+        down.append(np.nextafter(down[-1], np.float32(-np.inf), dtype=np.float32))
+    g = np.random.default_rng(3)
+    special = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-38, -1e-38, np.inf, -np.inf, np.nan, lo, hi, 3e38, -3e38], np.float32)
+    # the index arithmetic rounds (x - lo) to the spacing of floats near (hi - lo) / 2: values within a few
+    # of those spacings of the break point are where a compare against the break point itself would
+    # disagree with the index, so they are swept densely
+    ulp_at_half = np.float32(hi - lo) * np.float32(2.0 ** -24)
+    near = (mid + ulp_at_half * np.linspace(-4.0, 4.0, 3001)).astype(np.float32)
+    vals = np.concatenate([np.array(around + down, np.float32), special, near,
+                           (mid + g.standard_normal(400) * 1e-6).astype(np.float32)])
+    N = (vals.size + 127) // 128 * 128
+    bias = np.zeros(N, np.float32)
+    bias[:vals.size] = vals
+    M, K = 256, 64
+    A = np.zeros((M, K), np.int8)
+    Wm = np.zeros((N, K), np.int8)
+    for inv in (1e9, 3.0):
+        r = oracle.gemm_pwl(A[:2], Wm, bias=bias, alpha=1.0, table=ot[0], out_inv_scale=inv)
+        oq = torch.empty((M, N), dtype=torch.int8, device=DEV)
+        nm.nm_gemm_pwl(dev(A), dev(Wm), bias=dev(bias), alpha=1.0, tables=dt, table_idx=0, out_inv_scale=inv, out_q=oq)
+        got = host(oq)
+        assert_exact(got[:2], r["q"], f"two-segment table [{lo}, {hi}], scale {inv}")
+        assert np.all(got == got[0])
+    assert len(np.unique(r["seg"])) == 2
+    # the sweep does contain values left of the break point that the index puts into segment 1
+    seg_of = dict(zip(bias.tolist(), r["seg"][0].tolist()))
+    assert any(v < float(mid) and s == 1 for v, s in seg_of.items() if v == v)
+
+
 # ---- attention products -----------------------------------------------------------------------
 
 @pytest.mark.parametrize("B,S,H,heads", [(1, 64, 128, 2), (3, 40, 96, 3), (2, 128, 768, 12), (1, 200, 64, 1),
